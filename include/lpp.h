@@ -1,0 +1,167 @@
+/*
+ * lpp.h -- C ABI of the static-tree relaxed-verification step (LANTERN++) for one
+ * AMD MI355X (gfx950).
+ *
+ * The step verifies a fixed-topology draft tree against the target model in one
+ * pass (paper Sec. 2.1 and App. A.2 "Tree drafting and decoding") and applies the
+ * relaxed acceptance rule with the multiplicative bound (paper Sec. 4), falling
+ * back to residual resampling on rejection (Sec. 2.2, App. A.2 Eq. 2).
+ *
+ * Conventions
+ *   - Every pointer is tagged [host] or [device] below.  Device buffers are owned
+ *     by the caller, must live on the current HIP device and must stay valid
+ *     until the work enqueued on `stream` has completed.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they never synchronise and never allocate device
+ *     memory, except lpp_tree_create / lpp_tree_destroy.
+ *   - Every call validates its arguments on the host first and returns a status;
+ *     nothing is enqueued unless the status is LPP_OK.  No call throws.
+ *   - `ws` is caller-provided device scratch of at least the size returned by the
+ *     matching *_workspace query (256-byte aligned).  Its contents are undefined
+ *     between calls; two calls that share one workspace must be ordered on a stream.
+ *   - Rows: a tree has M = N+1 rows; row 0 is the root (the last committed token),
+ *     rows 1..N are the drafted nodes.
+ */
+#ifndef LPP_H_
+#define LPP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  LPP_OK = 0,
+  LPP_EINVAL = 1,        /* bad argument (null pointer, size out of range, malformed tree) */
+  LPP_EUNSUPPORTED = 2,  /* well-formed but outside what the kernels implement              */
+  LPP_ENOWORKSPACE = 3,  /* ws is NULL or ws_bytes is smaller than the query's answer       */
+  LPP_EHIP = 4           /* a HIP runtime call failed (no device, launch failure, ...)      */
+};
+
+enum { LPP_F32 = 0, LPP_BF16 = 1 };
+
+/* Limits of this implementation. */
+#define LPP_MAX_ROWS   256     /* M                                     */
+#define LPP_MAX_VOCAB  32768   /* V of lpp_relaxed_verify               */
+#define LPP_MAX_K      4096    /* k of lpp_build_neighbours             */
+
+const char* lpp_strerror(int32_t status);   /* static string, never NULL */
+const char* lpp_version(void);
+
+/* ------------------------------------------------------------------ tree ---
+ * Static draft-tree topology (paper Sec. 2.1 "static tree drafting"; App. B
+ * "Static Tree Structures").  parent_host [host]: M entries, parent[0] = -1,
+ * 0 <= parent[i] < i for i >= 1.  Children of a row are tried in ascending row
+ * index.  The library copies what it needs (child lists, depths, ancestor
+ * bitmasks: bit t of row i set iff t == i or t is an ancestor of i) to the
+ * current device; with no HIP device present the handle is host-only: it can be
+ * queried and passed to argument validation, and compute calls return LPP_EHIP.
+ * Errors: LPP_EINVAL (null, M < 1, M > LPP_MAX_ROWS, malformed parent),
+ * LPP_EHIP (allocation or copy failed).
+ */
+typedef struct lpp_tree lpp_tree;
+int32_t lpp_tree_create(const int32_t* parent_host, int32_t M, lpp_tree** out);
+int32_t lpp_tree_destroy(lpp_tree* tree);
+/* Any output pointer may be NULL.  depth = number of levels below the root. */
+int32_t lpp_tree_info(const lpp_tree* tree, int32_t* M, int32_t* depth,
+                      int32_t* n_parents, int32_t* max_children);
+
+/* ------------------------------------------------------ neighbour build ---
+ * Latent-space neighbourhoods B_k(x) of every code (paper Sec. 2.2: "its k
+ * nearest neighbors in latent space"; reused by Sec. 4).
+ *   E      [device] float32 [V, D] row-major codebook; the caller L2-normalises
+ *          the rows, so the inner product used here is the cosine similarity.
+ *   neigh  [device] int32 [V, k] out; row x = B_k(x), nearest first, x itself in
+ *          slot 0.  Order is by the similarity evaluated in float64 (the D
+ *          products added one after the other in index order), ties to the lower
+ *          index -- a deterministic, machine-independent result.
+ * One-time per codebook.  Errors: LPP_EINVAL (null, V < 1, D < 1, k < 1, k > V),
+ * LPP_EUNSUPPORTED (k > LPP_MAX_K, D > 4096, V > 65536), LPP_ENOWORKSPACE, LPP_EHIP.
+ * A codebook so degenerate that more than k + 1024 codes tie with the k-th
+ * neighbour of some code (within float32 rounding) is still handled exactly by a
+ * slower per-row path.
+ */
+size_t  lpp_build_neighbours_workspace(int32_t V, int32_t D, int32_t k);
+int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, int32_t k,
+                             int32_t* neigh, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------- tree attention ---
+ * One layer of tree-masked decode attention for the flattened tree (paper
+ * Sec. 2.1: "flattened and verified ... with an appropriate attention mask";
+ * App. A.2: the mask hides every non-ancestor node).  For batch item b, head h,
+ * row i:  out[b,h,i,:] = softmax_j(scale * <q[b,h,i], K_j>) V_j  over the keys
+ * j in { cached positions [0, seq_len[b]) } U { tree rows t : t == i or t is an
+ * ancestor of i }.
+ *   dtype     LPP_F32 or LPP_BF16: element type of q, k_cache, v_cache, k_tree, v_tree
+ *   q, k_tree, v_tree   [device] [B, H, M, Dh] contiguous
+ *   k_cache, v_cache    [device] [B, H, S, Dh] contiguous (multi-head: H_kv = H)
+ *   seq_len   [device] int32 [B] or NULL (= S for every item); values are clamped to [0, S]
+ *   scale     0 selects 1/sqrt(Dh)
+ *   out       [device] float32 [B, H, M, Dh]
+ * Softmax and accumulation are float32; bf16 inputs are multiplied on the matrix
+ * cores.  Errors: LPP_EINVAL (null, B/H/S/Dh < 1 -- S = 0 is allowed), LPP_EUNSUPPORTED
+ * (Dh not 64 or 128, dtype unknown), LPP_ENOWORKSPACE, LPP_EHIP.
+ */
+size_t  lpp_tree_attention_workspace(const lpp_tree* tree, int32_t B, int32_t H,
+                                     int32_t S, int32_t Dh);
+int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype,
+                           const void* q, const void* k_cache, const void* v_cache,
+                           const void* k_tree, const void* v_tree, const int32_t* seq_len,
+                           int32_t B, int32_t H, int32_t S, int32_t Dh, float scale,
+                           float* out, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------- relaxed verify ---
+ * Softmax of every row, relaxed acceptance of every drafted node and the walk
+ * down the tree (paper Sec. 4; Sec. 2.2; App. A.2 Eq. 1-2).  For row P with
+ * children c_1 < c_2 < ... (tokens x^ = tokens[b, c]):
+ *     q = softmax(target_logits[b,P]), p = softmax(drafter_logits[b,P]), r <- q
+ *     for each child:  A = longest nearest-first prefix of B_k(x^) with
+ *                          sum_{x in A} r(x) < lambda * r(x^)   (x^ always in A)
+ *                      mass = sum_A r,  ratio = mass / p(x^),
+ *                      decision = (u_accept * p(x^) < mass)
+ *                      r <- normalise([r' - p]_+), r' = r with A's mass moved onto x^
+ *     final_tok_all[b,P] = inverse-CDF draw from r with u_final[b,P]
+ *                          (a leaf draws its bonus token from q)
+ * Each row is evaluated for the outcome "all earlier siblings rejected", which
+ * involves no uniform; the walk then follows the first accepted child per level.
+ *   target_logits, drafter_logits  [device] float32 [B, M, ldv]; image token x is
+ *        column vocab_offset + x; columns outside [vocab_offset, vocab_offset+V)
+ *        must be -inf by contract and are not read; drafter rows of leaves are
+ *        never read (drafter_logits may be NULL if the tree has no drafted node).
+ *   tokens    [device] int32 [B, M], values in [0, V) (clamped otherwise); tokens[b,0] ignored
+ *   neigh     [device] int32 [V, kstride], first k columns used, slot 0 of row x is x
+ *   lambda    bound factor; values <= 1 admit no neighbour (plain speculative sampling)
+ *   u_accept, u_final   [device] float32 [B, M] in [0,1), supplied by the caller
+ *   out       see lpp_verify_out; accept_len, path and final_token are required,
+ *             the per-node arrays may be NULL.
+ * Errors: LPP_EINVAL (null, B < 1, V < 1, k < 1, k > kstride, k > V,
+ * vocab_offset < 0, vocab_offset + V > ldv, lambda NaN), LPP_EUNSUPPORTED
+ * (V > LPP_MAX_VOCAB), LPP_ENOWORKSPACE, LPP_EHIP.
+ */
+typedef struct lpp_verify_out {
+  int32_t* accept_len;     /* [device] [B]        number of accepted drafted nodes            */
+  int32_t* path;           /* [device] [B, depth] accepted rows root-to-leaf, -1 padded       */
+  int32_t* final_token;    /* [device] [B]        token emitted after the accepted path       */
+  uint8_t* decision;       /* [device] [B, M]     accept test of every node (row 0 unused: 0) */
+  float*   ratio;          /* [device] [B, M]     mass / p(x^)                                */
+  float*   mass;           /* [device] [B, M]     aggregated target mass                      */
+  int32_t* n_agg;          /* [device] [B, M]     |A|                                         */
+  float*   q_tok;          /* [device] [B, M]     r(x^) seen by the node                      */
+  float*   p_tok;          /* [device] [B, M]     p(x^)                                       */
+  int32_t* final_tok_all;  /* [device] [B, M]     draw of every row if the walk stops there   */
+} lpp_verify_out;
+
+size_t  lpp_relaxed_verify_workspace(const lpp_tree* tree, int32_t B, int32_t V, int32_t k);
+int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_logits,
+                           const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                           int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
+                           int32_t kstride, int32_t k, float lambda,
+                           const float* u_accept, const float* u_final,
+                           const lpp_verify_out* out, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LPP_H_ */

@@ -1,0 +1,141 @@
+"""ctypes binding of liblpp.so: argument marshalling only.
+
+Function names and argument order follow include/lpp.h.  Device buffers are
+torch tensors on the current HIP device (PyTorch is used for device memory and
+streams only); every step of the path runs in the library's kernels.  There is
+no fallback: a missing library raises at import of this module's loader.
+"""
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblpp.so")
+
+LPP_OK, LPP_EINVAL, LPP_EUNSUPPORTED, LPP_ENOWORKSPACE, LPP_EHIP = range(5)
+LPP_F32, LPP_BF16 = 0, 1
+
+
+class LppError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lib().lpp_strerror(status).decode()} (status {status})")
+
+
+class VerifyOut(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("accept_len", "path", "final_token", "decision", "ratio", "mass", "n_agg",
+                 "q_tok", "p_tok", "final_tok_all")]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load liblpp.so (built in-tree by ``python -m paper_2502_06352_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run __graft_entry__.build() "
+                          "(there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
+    L.lpp_strerror.restype = C.c_char_p; L.lpp_strerror.argtypes = [i32]
+    L.lpp_version.restype = C.c_char_p; L.lpp_version.argtypes = []
+    L.lpp_tree_create.restype = i32; L.lpp_tree_create.argtypes = [vp, i32, C.POINTER(vp)]
+    L.lpp_tree_destroy.restype = i32; L.lpp_tree_destroy.argtypes = [vp]
+    L.lpp_tree_info.restype = i32; L.lpp_tree_info.argtypes = [vp] + [C.POINTER(i32)] * 4
+    L.lpp_build_neighbours_workspace.restype = sz
+    L.lpp_build_neighbours_workspace.argtypes = [i32, i32, i32]
+    L.lpp_build_neighbours.restype = i32
+    L.lpp_build_neighbours.argtypes = [vp, i32, i32, i32, vp, vp, sz, vp]
+    L.lpp_tree_attention_workspace.restype = sz
+    L.lpp_tree_attention_workspace.argtypes = [vp, i32, i32, i32, i32]
+    L.lpp_tree_attention.restype = i32
+    L.lpp_tree_attention.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, vp, sz, vp]
+    L.lpp_relaxed_verify_workspace.restype = sz
+    L.lpp_relaxed_verify_workspace.argtypes = [vp, i32, i32, i32]
+    L.lpp_relaxed_verify.restype = i32
+    L.lpp_relaxed_verify.argtypes = [vp, vp, vp, i64, i32, i32, i32, vp, vp, i32, i32, f32, vp, vp,
+                                     C.POINTER(VerifyOut), vp, sz, vp]
+    _lib = L
+    return L
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    s = int(getattr(stream, "cuda_stream", stream))
+    return s or None
+
+
+def _check(status: int, where: str) -> None:
+    if status != LPP_OK:
+        raise LppError(status, where)
+
+
+class Tree:
+    """Owner of an ``lpp_tree*`` (lpp_tree_create / lpp_tree_destroy)."""
+
+    def __init__(self, parent):
+        parent = np.ascontiguousarray(parent, dtype=np.int32)
+        self.parent = parent
+        self.handle = C.c_void_p()
+        _check(lib().lpp_tree_create(parent.ctypes.data, len(parent), C.byref(self.handle)), "lpp_tree_create")
+        v = [C.c_int32() for _ in range(4)]
+        _check(lib().lpp_tree_info(self.handle, *[C.byref(x) for x in v]), "lpp_tree_info")
+        self.M, self.depth, self.n_parents, self.max_children = [x.value for x in v]
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().lpp_tree_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+
+def lpp_build_neighbours_workspace(V: int, D: int, k: int) -> int:
+    return int(lib().lpp_build_neighbours_workspace(V, D, k))
+
+
+def lpp_build_neighbours(E, k: int, neigh, ws, stream=None) -> None:
+    V, D = E.shape
+    _check(lib().lpp_build_neighbours(_ptr(E), V, D, k, _ptr(neigh), _ptr(ws),
+                                      0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
+           "lpp_build_neighbours")
+
+
+def lpp_tree_attention_workspace(tree: Tree, B: int, H: int, S: int, Dh: int) -> int:
+    return int(lib().lpp_tree_attention_workspace(tree.handle, B, H, S, Dh))
+
+
+def lpp_tree_attention(tree: Tree, dtype: int, q, k_cache, v_cache, k_tree, v_tree, seq_len,
+                       B: int, H: int, S: int, Dh: int, scale: float, out, ws, stream=None) -> None:
+    _check(lib().lpp_tree_attention(tree.handle, dtype, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree),
+                                    _ptr(v_tree), _ptr(seq_len), B, H, S, Dh, scale, _ptr(out), _ptr(ws),
+                                    0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
+           "lpp_tree_attention")
+
+
+def lpp_relaxed_verify_workspace(tree: Tree, B: int, V: int, k: int) -> int:
+    return int(lib().lpp_relaxed_verify_workspace(tree.handle, B, V, k))
+
+
+def lpp_relaxed_verify(tree: Tree, target_logits, drafter_logits, ldv: int, vocab_offset: int, V: int,
+                       B: int, tokens, neigh, kstride: int, k: int, lam: float, u_accept, u_final,
+                       out: dict, ws, stream=None) -> None:
+    """``out`` maps lpp_verify_out field names to tensors (missing / None = not wanted)."""
+    vo = VerifyOut(**{n: _ptr(out.get(n)) for n, _ in VerifyOut._fields_})
+    _check(lib().lpp_relaxed_verify(tree.handle, _ptr(target_logits), _ptr(drafter_logits), ldv, vocab_offset,
+                                    V, B, _ptr(tokens), _ptr(neigh), kstride, k, lam, _ptr(u_accept),
+                                    _ptr(u_final), C.byref(vo), _ptr(ws),
+                                    0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
+           "lpp_relaxed_verify")

@@ -1,0 +1,38 @@
+// Internal declarations shared by the translation units of liblpp (not installed).
+#ifndef LPP_INTERNAL_H_
+#define LPP_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+
+#include "lpp.h"
+
+// Host-side image of a static draft tree plus its device copy.
+struct lpp_tree {
+  int32_t M = 0;             // rows (root + drafted nodes)
+  int32_t depth = 0;         // levels below the root
+  int32_t n_parents = 0;     // rows with at least one child
+  int32_t max_children = 0;
+  int32_t words = 0;         // 64-bit words per ancestor bitmask
+  std::vector<int32_t> parent, row_depth, child_ptr, child_idx;
+  std::vector<uint64_t> anc; // [M * words]
+  // device copies (null for a host-only handle)
+  int device = -1;
+  int32_t* d_child_ptr = nullptr;  // [M + 1]
+  int32_t* d_child_idx = nullptr;  // [max(N, 1)]
+  uint64_t* d_anc = nullptr;       // [M * words]
+};
+
+#define LPP_HIP_TRY(expr)                      \
+  do {                                         \
+    hipError_t e_ = (expr);                    \
+    if (e_ != hipSuccess) {                    \
+      (void)hipGetLastError();                 \
+      return LPP_EHIP;                         \
+    }                                          \
+  } while (0)
+
+static inline size_t lpp_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+#endif  // LPP_INTERNAL_H_

@@ -1,0 +1,130 @@
+"""Helpers of the GPU parity tests: upload seeded inputs, call the C ABI through
+the binding, bring results back, compare with the oracle under the stated rules."""
+import numpy as np
+import torch
+
+import paper_2502_06352_amd as lpp
+from oracle import build_neighbours, relaxed_verify
+from workloads import children_lists
+
+DEV = "cuda:0"
+
+
+def dev(x, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to(DEV)
+
+
+def bf16_dev(bits):
+    """uint16 bit patterns -> torch.bfloat16 tensor on the device."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def sparse_neighbour_table(E, k, tokens, V):
+    """Oracle neighbour rows for the drafted tokens only; other rows hold a valid
+    but arbitrary list (x, x+1, ...) that no node of this input reads."""
+    neigh = ((np.arange(V, dtype=np.int64)[:, None] + np.arange(k, dtype=np.int64)[None, :]) % V).astype(np.int32)
+    used = np.unique(tokens)
+    neigh[used] = build_neighbours(E, k, rows=used)
+    return neigh
+
+
+def run_verify(tree, x, neigh, cfgV, off, ldv, k, lam, want_all=True, stream=None):
+    B, M = x["tokens"].shape
+    depth = max(tree.depth, 1)
+    d = {n: dev(x[n]) for n in ("target_logits", "drafter_logits", "tokens", "u_accept", "u_final")}
+    dn = dev(neigh)
+    out = {"accept_len": torch.full((B,), -7, dtype=torch.int32, device=DEV),
+           "path": torch.full((B, depth), -7, dtype=torch.int32, device=DEV),
+           "final_token": torch.full((B,), -7, dtype=torch.int32, device=DEV)}
+    if want_all:
+        out.update(decision=torch.full((B, M), 9, dtype=torch.uint8, device=DEV),
+                   ratio=torch.zeros((B, M), device=DEV), mass=torch.zeros((B, M), device=DEV),
+                   n_agg=torch.zeros((B, M), dtype=torch.int32, device=DEV),
+                   q_tok=torch.zeros((B, M), device=DEV), p_tok=torch.zeros((B, M), device=DEV),
+                   final_tok_all=torch.full((B, M), -7, dtype=torch.int32, device=DEV))
+    ws = torch.empty(lpp.lpp_relaxed_verify_workspace(tree, B, cfgV, k), dtype=torch.uint8, device=DEV)
+    lpp.lpp_relaxed_verify(tree, d["target_logits"], d["drafter_logits"], ldv, off, cfgV, B, d["tokens"], dn,
+                           neigh.shape[1], k, lam, d["u_accept"], d["u_final"], out, ws, stream)
+    torch.cuda.synchronize()
+    return {n: t.cpu().numpy() for n, t in out.items()}
+
+
+def compare_verify(parent, x, neigh, V, off, k, lam, got, rel=1e-4, tie=1e-5, cdf_tol=2e-6):
+    """Compare every output with the float64 oracle.  Returns a report dict.
+
+    Rules: decisions bit-exact unless |u - ratio| < tie (counted); mass / ratio /
+    q_tok / p_tok within rel; n_agg equal unless the oracle's bound margin shows a
+    float32-level tie at the stopping sum (counted); after such a tie the later
+    siblings and the parent's draw are not comparable and are skipped (counted);
+    final tokens must bracket u*Z in the oracle's float64 CDF within cdf_tol*Z.
+    """
+    want = relaxed_verify(parent, x["target_logits"], x["drafter_logits"], off, V, x["tokens"], neigh, k, lam,
+                          x["u_accept"], x["u_final"], keep_final_cdf=True)
+    kids = children_lists(parent)
+    B, M = x["tokens"].shape
+    rep = dict(nodes=0, near_tie_decisions=0, nagg_ties=0, skipped_after_tie=0, final_exact=0, final_rows=0,
+               max_rel=0.0, walks_compared=0)
+    for b in range(B):
+        tainted_rows = set()
+        decision_uncertain = False
+        for P in range(M):
+            row_tainted = False
+            for c in kids[P]:
+                if row_tainted:
+                    rep["skipped_after_tie"] += 1
+                    decision_uncertain = True
+                    continue
+                rep["nodes"] += 1
+                if got["n_agg"][b, c] != want["n_agg"][b, c]:
+                    assert want["bound_margin"][b, c] < 1e-4, (
+                        f"n_agg differs without a tie: b={b} c={c} got {got['n_agg'][b, c]} "
+                        f"want {want['n_agg'][b, c]} margin {want['bound_margin'][b, c]}")
+                    assert abs(int(got["n_agg"][b, c]) - int(want["n_agg"][b, c])) == 1
+                    rep["nagg_ties"] += 1
+                    row_tainted = True
+                    decision_uncertain = True
+                    continue
+                for name in ("mass", "q_tok", "p_tok", "ratio"):
+                    g, w = float(got[name][b, c]), float(want[name][b, c])
+                    err = abs(g - w) / max(abs(w), 1e-300)
+                    rep["max_rel"] = max(rep["max_rel"], err)
+                    assert err <= rel, f"{name} b={b} c={c}: got {g} want {w} rel {err}"
+                if got["decision"][b, c] != want["decision"][b, c]:
+                    u = float(x["u_accept"][b, c])
+                    assert abs(u - want["ratio"][b, c]) < tie, (
+                        f"decision differs away from a tie: b={b} c={c} u={u} ratio={want['ratio'][b, c]}")
+                    rep["near_tie_decisions"] += 1
+                    decision_uncertain = True
+            if row_tainted:
+                tainted_rows.add(P)
+                continue
+            rep["final_rows"] += 1
+            xg = int(got["final_tok_all"][b, P])
+            assert 0 <= xg < V
+            cdf = want["final_cdf"][b, P]
+            Z = cdf[-1]
+            tgt = float(x["u_final"][b, P]) * Z
+            lo = cdf[xg - 1] if xg > 0 else 0.0
+            assert lo - cdf_tol * Z <= tgt <= cdf[xg] + cdf_tol * Z, (
+                f"final token outside its CDF bracket: b={b} P={P} got {xg} want {want['final_tok_all'][b, P]}")
+            assert cdf[xg] - lo > 0, "drew a zero-probability token"
+            rep["final_exact"] += int(xg == want["final_tok_all"][b, P])
+        # the walk must be the walk of the decisions the GPU itself reports
+        cur, n, path = 0, 0, []
+        while True:
+            nxt = next((c for c in kids[cur] if got["decision"][b, c]), None)
+            if nxt is None:
+                break
+            path.append(nxt); cur = nxt; n += 1
+        assert got["accept_len"][b] == n
+        assert got["path"][b].tolist() == path + [-1] * (got["path"].shape[1] - n)
+        assert got["final_token"][b] == got["final_tok_all"][b, cur]
+        if not decision_uncertain:
+            rep["walks_compared"] += 1
+            assert got["accept_len"][b] == want["accept_len"][b]
+            assert np.array_equal(got["path"][b], want["path"][b])
+        assert np.all(got["decision"][b, 0] == 0)
+    return rep
