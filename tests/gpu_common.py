@@ -128,3 +128,28 @@ def compare_verify(parent, x, neigh, V, off, k, lam, got, rel=1e-4, tie=1e-5, cd
             assert np.array_equal(got["path"][b], want["path"][b])
         assert np.all(got["decision"][b, 0] == 0)
     return rep
+
+
+def run_attention(tree, att, cfg, seq_len=None, S=None, stream=None):
+    """Upload one attention input set and call lpp_tree_attention; returns float32 [B,H,M,Dh]."""
+    B, H, M, Dh = att["q"].shape
+    S = att["kc"].shape[2] if S is None else S
+    if cfg.kv_dtype == "bf16":
+        t = {n: bf16_dev(att[n + "_bits"]) for n in ("q", "kc", "vc", "kt", "vt")}
+        dtype = lpp.LPP_BF16
+    else:
+        t = {n: dev(att[n]) for n in ("q", "kc", "vc", "kt", "vt")}
+        dtype = lpp.LPP_F32
+    sl = None if seq_len is None else dev(np.asarray(seq_len, dtype=np.int32))
+    out = torch.full((B, H, M, Dh), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(lpp.lpp_tree_attention_workspace(tree, B, H, S, Dh), 256), dtype=torch.uint8, device=DEV)
+    lpp.lpp_tree_attention(tree, dtype, t["q"], t["kc"] if S > 0 else None, t["vc"] if S > 0 else None,
+                           t["kt"], t["vt"], sl, B, H, S, Dh, 0.0, out, ws, stream)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def attention_error(got, want):
+    """max over rows of |got - want| / (|want| + max|want| over the row's Dh vector)."""
+    scale = np.abs(want) + np.abs(want).max(axis=-1, keepdims=True)
+    return float(np.max(np.abs(got - want) / scale))
