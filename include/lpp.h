@@ -78,7 +78,7 @@ int32_t lpp_tree_info(const lpp_tree* tree, int32_t* M, int32_t* depth,
  *          products added one after the other in index order), ties to the lower
  *          index -- a deterministic, machine-independent result.
  * One-time per codebook.  Errors: LPP_EINVAL (null, V < 1, D < 1, k < 1, k > V),
- * LPP_EUNSUPPORTED (k > LPP_MAX_K, D > 4096, V > 65536), LPP_ENOWORKSPACE, LPP_EHIP.
+ * LPP_EUNSUPPORTED (k > LPP_MAX_K, D > 256, V > 65536), LPP_ENOWORKSPACE, LPP_EHIP.
  * A codebook so degenerate that more than k + 1024 codes tie with the k-th
  * neighbour of some code (within float32 rounding) is still handled exactly by a
  * slower per-row path.

@@ -1,5 +1,428 @@
+// Latent-space neighbourhoods B_k(x) of every code of a VQ codebook (paper
+// Sec. 2.2: the k nearest neighbours of a token in latent space; reused by Sec. 4).
+//
+// The result is defined by the float64 inner product (products added in index
+// order) with ties to the lower index, so it does not depend on how the matrix
+// cores round.  Three kernels:
+//   pack    zero-padded copy of the codebook (rows of DP floats, DP = 16..256 a power of two >= D), row
+//           norms and their maximum (for the rounding bound below).
+//   select  the dense V x V contraction on the fp32 matrix cores (MFMA 16x16x4),
+//           swept twice per block of 64 codes and never written out: sweep 1
+//           histograms each row's similarities into 1024 bins and finds the bin
+//           b* holding the (k-1)-th largest; sweep 2 appends every code whose bin
+//           is >= b* - 1 to the row's candidate list.
+//   rank    per row: exact float64 keys of the candidates (FMA chain in index
+//           order), bitonic sort by (key desc, index asc) in LDS, write the row.
+// Why the candidate list is enough: a code that is not a candidate has an
+// approximate similarity below the lower edge e of bin b* - 1, hence an exact key
+// below e + eps, eps bounding the matrix-core rounding.  If the (k-1)-th exact key
+// among the candidates is >= e + eps, no outsider can belong to the row.  Rows
+// that fail this test, or overflow the candidate list, take an exact (slow)
+// radix-select path over all V codes instead.
+#include <limits.h>
+#include <math.h>
+
 #include "lpp_internal.h"
-extern "C" size_t lpp_build_neighbours_workspace(int32_t, int32_t, int32_t) { return 256; }
-extern "C" int32_t lpp_build_neighbours(const float*, int32_t, int32_t, int32_t, int32_t*, void*, size_t, void*) {
-  return LPP_EUNSUPPORTED;
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBins = 1024;
+constexpr float kBinScale = 512.0f;           // bin = floor((s + 1) * 512), clamped
+constexpr int kSelWaves = 4;
+constexpr int kSelRows = kSelWaves * 16;      // codes per select block
+constexpr int kRankThreads = 256;
+constexpr int kSlack = 1024;                  // candidate list = k - 1 + slack (rounded)
+
+struct KnnArgs {
+  const float* E;
+  int32_t V, D, DP, Vp, k, cap;
+  float* Ep;            // [Vp][DP]
+  float* norms;         // [Vp]
+  uint32_t* maxnorm;    // float bits
+  int32_t* bstar;       // [Vp]
+  int32_t* cnt;         // [Vp]
+  uint16_t* cand;       // [V][cap]
+  int32_t* neigh;       // [V][k]
+};
+
+__global__ void knn_init_kernel(KnnArgs a) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *a.maxnorm = 0u;
+}
+
+// One wave per row: padded copy, norm, max norm.
+__global__ __launch_bounds__(256) void knn_pack_kernel(KnnArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= a.Vp) return;
+  float ss = 0.f;
+  for (int d = lane; d < a.DP; d += 64) {
+    float v = 0.f;
+    if (row < a.V && d < a.D) v = a.E[(int64_t)row * a.D + d];
+    a.Ep[(int64_t)row * a.DP + d] = v;
+    ss += v * v;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  if (lane == 0) {
+    const float n = sqrtf(ss);
+    a.norms[row] = n;
+    if (row < a.V) atomicMax(a.maxnorm, __float_as_uint(n));
+  }
+}
+
+__device__ __forceinline__ int sim_bin(float s) {
+  const float x = (s + 1.0f) * kBinScale;
+  int b = (int)floorf(x);
+  b = x != x ? 0 : b;
+  return min(max(b, 0), kBins - 1);
+}
+
+// NS4 = float4 loads per lane and code (DP = 16 * NS4).  Contraction slot (step, g)
+// of the 16x16x4 MFMA is dimension 16*(step/4) + 4*g + step%4 on both operands.
+template <int NS4>
+__global__ __launch_bounds__(kSelWaves * 64) void knn_select_kernel(KnnArgs a) {
+  extern __shared__ uint32_t s_hist[];          // [kSelRows][kBins/2], two 16-bit counts per word
+  __shared__ int s_cnt[kSelRows];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l16 = lane & 15, g4 = lane >> 4;
+  const int row0 = blockIdx.x * kSelRows + wave * 16;   // this wave's 16 query codes
+  const int qrow = row0 + l16;                          // the lane's query code (B operand column)
+  const int DP = a.DP, V = a.V;
+  const int kk = a.k - 1;                               // neighbours besides the code itself
+
+  f32x4 qv[NS4];
+#pragma unroll
+  for (int s = 0; s < NS4; ++s)
+    qv[s] = *reinterpret_cast<const f32x4*>(a.Ep + (int64_t)qrow * DP + 16 * s + 4 * g4);
+
+  uint32_t* hist = s_hist + (wave * 16) * (kBins / 2);
+  for (int i = lane; i < 16 * (kBins / 2); i += 64) hist[i] = 0u;
+  if (lane < 16) s_cnt[wave * 16 + lane] = 0;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  int bstar = 0;
+  for (int phase = 0; phase < 2; ++phase) {
+    for (int c0 = 0; c0 < a.Vp; c0 += 16) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      const float* arow = a.Ep + (int64_t)(c0 + l16) * DP + 4 * g4;
+#pragma unroll
+      for (int s = 0; s < NS4; ++s) {
+        const f32x4 av = *reinterpret_cast<const f32x4*>(arow + 16 * s);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[0], qv[s][0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[1], qv[s][1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[2], qv[s][2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[3], qv[s][3], acc, 0, 0, 0);
+      }
+      // lane holds sim(code c0 + 4*g4 + r, query qrow), r = 0..3
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int code = c0 + 4 * g4 + r;
+        if (code >= V || code == qrow || qrow >= V) continue;
+        const int bin = sim_bin(acc[r]);
+        if (phase == 0) {
+          atomicAdd(&hist[l16 * (kBins / 2) + (bin >> 1)], (bin & 1) ? 65536u : 1u);
+        } else if (bin >= bstar - 1) {
+          const int pos = atomicAdd(&s_cnt[wave * 16 + l16], 1);
+          if (pos < a.cap) a.cand[(int64_t)qrow * a.cap + pos] = (uint16_t)code;
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (phase == 0) {
+      // b* of each of the wave's 16 rows: highest bin whose count-from-the-top reaches kk
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t* h = hist + r * (kBins / 2);
+        // lane covers bins [1023 - 16*lane - 15, 1023 - 16*lane], scanned downwards
+        int cntv[16];
+        int local = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const uint32_t w = h[(kBins / 2 - 1) - 8 * lane - j];   // bins (hi, lo) = (odd, even)
+          cntv[2 * j] = (int)(w >> 16);
+          cntv[2 * j + 1] = (int)(w & 0xFFFFu);
+          local += cntv[2 * j] + cntv[2 * j + 1];
+        }
+        int incl = local;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int t = __shfl_up(incl, o);
+          if (lane >= o) incl += t;
+        }
+        const unsigned long long bal = __ballot(incl >= kk);
+        int bs = 0;
+        if (bal) {
+          const int fl = __ffsll((long long)bal) - 1;
+          int run = __shfl(incl - local, fl);
+          int found = 0;
+          if (lane == fl) {
+            found = kBins - 1 - 16 * lane - 15;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              run += cntv[j];
+              if (run >= kk) { found = kBins - 1 - 16 * lane - j; break; }
+            }
+          }
+          bs = __shfl(found, fl);
+        }
+        if (l16 == r) bstar = bs;
+      }
+      if (g4 == 0 && qrow < a.Vp) a.bstar[qrow] = bstar;
+    }
+  }
+  if (lane < 16 && row0 + lane < a.Vp) a.cnt[row0 + lane] = s_cnt[wave * 16 + lane];
+}
+
+__device__ __forceinline__ uint64_t orderable(double x) {
+  const uint64_t u = (uint64_t)__double_as_longlong(x);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+
+// exact key of the pair (row i held in LDS as floats, code j): float64 FMA chain in index order
+__device__ __forceinline__ uint64_t exact_key(const float* ei, const float* Ep, int DP, int D, int j) {
+  const float* ej = Ep + (int64_t)j * DP;
+  double acc = 0.0;
+  for (int t0 = 0; t0 < D; t0 += 4) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(ej + t0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (t0 + e < D) acc = __builtin_fma((double)ei[t0 + e], (double)v[e], acc);
+  }
+  return orderable(acc);
+}
+
+// (key desc, idx asc) "a goes before b"
+__device__ __forceinline__ bool before(uint64_t ka, uint32_t ia, uint64_t kb, uint32_t ib) {
+  return ka > kb || (ka == kb && ia < ib);
+}
+
+// In-LDS bitonic sort of P (power of two) entries by (key desc, idx asc); ends with a barrier.
+__device__ void bitonic_sort(uint64_t* skey, uint32_t* sidx, int P, int tid) {
+  for (int size = 2; size <= P; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int t = tid; t < (P >> 1); t += kRankThreads) {
+        const int lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
+        const int hi = lo | stride;
+        const bool up = (lo & size) == 0;            // this run ends up in "before" order
+        const uint64_t k0 = skey[lo], k1 = skey[hi];
+        const uint32_t i0 = sidx[lo], i1 = sidx[hi];
+        const bool sw = up ? before(k1, i1, k0, i0) : before(k0, i0, k1, i1);
+        if (sw) { skey[lo] = k1; skey[hi] = k0; sidx[lo] = i1; sidx[hi] = i0; }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+__global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a) {
+  extern __shared__ unsigned char smem[];
+  __shared__ int s_hist[256];
+  __shared__ int s_misc[8];
+  const int tid = threadIdx.x;
+  const int i = blockIdx.x;
+  const int V = a.V, D = a.D, DP = a.DP, kk = a.k - 1;
+  int32_t* out = a.neigh + (int64_t)i * a.k;
+  if (kk == 0) {
+    if (tid == 0) out[0] = i;
+    return;
+  }
+  // P = power of two >= cap (set by the host through the dynamic LDS size)
+  int P = 1;
+  while (P < a.cap) P <<= 1;
+  uint64_t* skey = reinterpret_cast<uint64_t*>(smem);
+  uint32_t* sidx = reinterpret_cast<uint32_t*>(skey + P);
+  float* ei = reinterpret_cast<float*>(sidx + P);
+  for (int d = tid; d < DP; d += kRankThreads) ei[d] = a.Ep[(int64_t)i * DP + d];
+  __syncthreads();
+
+  const int n = a.cnt[i];
+  bool slow = n > a.cap || n < kk;          // list overflowed: only the exact path is safe
+  if (!slow) {
+    for (int c = tid; c < P; c += kRankThreads) {
+      if (c < n) {
+        const int j = a.cand[(int64_t)i * a.cap + c];
+        skey[c] = exact_key(ei, a.Ep, DP, D, j);
+        sidx[c] = (uint32_t)j;
+      } else {
+        skey[c] = 0ull;
+        sidx[c] = 0xFFFFFFFFu;
+      }
+    }
+    __syncthreads();
+    bitonic_sort(skey, sidx, P, tid);
+    // can a code outside the candidate list still belong to the row?
+    const int bs = a.bstar[i];
+    if (bs - 1 >= 1) {
+      const float edge = (float)(bs - 1) / kBinScale - 1.0f;      // lower edge of bin b* - 1
+      const float eps = (float)(DP + 4) * 1.1920929e-07f * a.norms[i] * __uint_as_float(*a.maxnorm) * 1.001f + 1e-37f;
+      slow = skey[kk - 1] < orderable((double)edge + (double)eps);
+    }
+    __syncthreads();
+  }
+  if (slow) {
+    // ---- exact path over all V codes: radix select of the kk-th largest key
+    uint64_t prefix = 0ull;
+    int need = kk;
+    for (int byte = 7; byte >= 0; --byte) {
+      s_hist[tid] = 0;
+      __syncthreads();
+      for (int j = tid; j < V; j += kRankThreads) {
+        if (j == i) continue;
+        const uint64_t K = exact_key(ei, a.Ep, DP, D, j);
+        const bool match = byte == 7 || (K >> (8 * (byte + 1))) == (prefix >> (8 * (byte + 1)));
+        if (match) atomicAdd(&s_hist[(int)((K >> (8 * byte)) & 255ull)], 1);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        int cum = 0, bsel = 0;
+        for (int bkt = 255; bkt >= 0; --bkt) {
+          if (cum + s_hist[bkt] >= need) { bsel = bkt; break; }
+          cum += s_hist[bkt];
+        }
+        s_misc[0] = bsel;
+        s_misc[1] = need - cum;
+      }
+      __syncthreads();
+      prefix |= (uint64_t)s_misc[0] << (8 * byte);
+      need = s_misc[1];
+      __syncthreads();
+    }
+    // prefix = exact kk-th largest key; keep everything above it plus the `need`
+    // lowest-index codes equal to it
+    const int n_gt = kk - need;
+    if (tid == 0) { s_misc[2] = 0; s_misc[3] = 0; }
+    for (int c = tid; c < P; c += kRankThreads) { skey[c] = 0ull; sidx[c] = 0xFFFFFFFFu; }
+    __syncthreads();
+    const int lane = tid & 63, wv = tid >> 6;
+    for (int j0 = 0; j0 < V; j0 += kRankThreads) {
+      const int j = j0 + tid;
+      uint64_t K = 0ull;
+      bool gt = false, eq = false;
+      if (j < V && j != i) {
+        K = exact_key(ei, a.Ep, DP, D, j);
+        gt = K > prefix;
+        eq = K == prefix;
+      }
+      if (gt) {
+        const int pos = atomicAdd(&s_misc[2], 1);
+        skey[pos] = K; sidx[pos] = (uint32_t)j;
+      }
+      // ordered compaction of the ties (ascending index)
+      const unsigned long long bal = __ballot(eq);
+      if (lane == 0) s_hist[wv] = __popcll(bal);
+      __syncthreads();
+      int base = s_misc[3];
+      for (int w = 0; w < wv; ++w) base += s_hist[w];
+      const int rank = base + __popcll(bal & ((1ull << lane) - 1ull));
+      if (eq && rank < need) { skey[n_gt + rank] = K; sidx[n_gt + rank] = (uint32_t)j; }
+      __syncthreads();
+      if (tid == 0) s_misc[3] += s_hist[0] + s_hist[1] + s_hist[2] + s_hist[3];
+      __syncthreads();
+    }
+    bitonic_sort(skey, sidx, P, tid);
+  }
+  if (tid == 0) out[0] = i;
+  for (int c = tid; c < kk; c += kRankThreads) out[1 + c] = (int32_t)sidx[c];
+}
+
+int32_t cap_for(int32_t k) { return (int32_t)lpp_align_up((size_t)(k - 1) + kSlack, 64); }
+
+struct KnnLayout {
+  size_t o_ep, o_norms, o_max, o_bstar, o_cnt, o_cand, total;
+  int32_t DP, Vp, cap;
+};
+
+KnnLayout knn_layout(int32_t V, int32_t D, int32_t k) {
+  KnnLayout L;
+  L.DP = 16;
+  while (L.DP < D) L.DP <<= 1;             // 16, 32, ..., 256
+  L.Vp = (int32_t)lpp_align_up((size_t)V, kSelRows);
+  L.cap = cap_for(k);
+  size_t o = 0;
+  L.o_ep = o;    o += lpp_align_up((size_t)L.Vp * L.DP * sizeof(float), 256);
+  L.o_norms = o; o += lpp_align_up((size_t)L.Vp * sizeof(float), 256);
+  L.o_max = o;   o += 256;
+  L.o_bstar = o; o += lpp_align_up((size_t)L.Vp * sizeof(int32_t), 256);
+  L.o_cnt = o;   o += lpp_align_up((size_t)L.Vp * sizeof(int32_t), 256);
+  L.o_cand = o;  o += lpp_align_up((size_t)V * L.cap * sizeof(uint16_t), 256);
+  L.total = o;
+  return L;
+}
+
+template <int NS4>
+int32_t launch_select(const KnnArgs& a, hipStream_t s) {
+  static bool attr_set = false;
+  const size_t lds = (size_t)kSelRows * (kBins / 2) * sizeof(uint32_t);
+  auto kern = knn_select_kernel<NS4>;
+  if (!attr_set) {
+    LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.Vp / kSelRows)), dim3(kSelWaves * 64), lds, s, a);
+  LPP_HIP_TRY(hipGetLastError());
+  return LPP_OK;
+}
+
+}  // namespace
+
+extern "C" size_t lpp_build_neighbours_workspace(int32_t V, int32_t D, int32_t k) {
+  if (V < 1 || D < 1 || k < 1 || k > V || k > LPP_MAX_K || D > 256 || V > 65536) return 0;
+  return knn_layout(V, D, k).total;
+}
+
+extern "C" int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, int32_t k, int32_t* neigh,
+                                        void* ws, size_t ws_bytes, void* stream) {
+  if (!E || !neigh) return LPP_EINVAL;
+  if (V < 1 || D < 1 || k < 1 || k > V) return LPP_EINVAL;
+  if (k > LPP_MAX_K || D > 256 || V > 65536) return LPP_EUNSUPPORTED;
+  const KnnLayout L = knn_layout(V, D, k);
+  if (!ws || ws_bytes < L.total) return LPP_ENOWORKSPACE;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) { (void)hipGetLastError(); return LPP_EHIP; }
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  unsigned char* w = reinterpret_cast<unsigned char*>(ws);
+  KnnArgs a;
+  a.E = E; a.V = V; a.D = D; a.DP = L.DP; a.Vp = L.Vp; a.k = k; a.cap = L.cap;
+  a.Ep = reinterpret_cast<float*>(w + L.o_ep);
+  a.norms = reinterpret_cast<float*>(w + L.o_norms);
+  a.maxnorm = reinterpret_cast<uint32_t*>(w + L.o_max);
+  a.bstar = reinterpret_cast<int32_t*>(w + L.o_bstar);
+  a.cnt = reinterpret_cast<int32_t*>(w + L.o_cnt);
+  a.cand = reinterpret_cast<uint16_t*>(w + L.o_cand);
+  a.neigh = neigh;
+
+  hipLaunchKernelGGL(knn_init_kernel, dim3(1), dim3(64), 0, s, a);
+  LPP_HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(knn_pack_kernel, dim3((unsigned)((L.Vp + 3) / 4)), dim3(256), 0, s, a);
+  LPP_HIP_TRY(hipGetLastError());
+  if (k > 1) {
+    int32_t st;
+    switch (L.DP / 16) {
+      case 1: st = launch_select<1>(a, s); break;
+      case 2: st = launch_select<2>(a, s); break;
+      case 4: st = launch_select<4>(a, s); break;
+      case 8: st = launch_select<8>(a, s); break;
+      case 16: st = launch_select<16>(a, s); break;
+      default: st = LPP_EUNSUPPORTED; break;
+    }
+    if (st != LPP_OK) return st;
+  }
+  static bool attr_set = false;
+  int P = 1;
+  while (P < L.cap) P <<= 1;
+  const size_t lds = (size_t)P * 12 + (size_t)L.DP * sizeof(float);
+  if (!attr_set) {
+    LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(knn_rank_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(knn_rank_kernel, dim3((unsigned)V), dim3(kRankThreads), lds, s, a);
+  LPP_HIP_TRY(hipGetLastError());
+  return LPP_OK;
 }

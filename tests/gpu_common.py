@@ -153,3 +153,15 @@ def attention_error(got, want):
     """max over rows of |got - want| / (|want| + max|want| over the row's Dh vector)."""
     scale = np.abs(want) + np.abs(want).max(axis=-1, keepdims=True)
     return float(np.max(np.abs(got - want) / scale))
+
+
+def run_knn(E, k):
+    V, D = E.shape
+    dE = dev(E)
+    neigh = torch.full((V, k), -1, dtype=torch.int32, device=DEV)
+    nbytes = lpp.lpp_build_neighbours_workspace(V, D, k)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    lpp.lpp_build_neighbours(dE, k, neigh, ws)
+    torch.cuda.synchronize()
+    return neigh.cpu().numpy()

@@ -1,0 +1,78 @@
+"""GPU parity: lpp_build_neighbours against the brute-force float64 oracle.
+Neighbour indices must be bit-exact (order included)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import paper_2502_06352_amd as lpp
+from oracle import build_neighbours
+from workloads import CONFIGS, make_codebook
+from gpu_common import run_knn
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_rows(E, k, got, rows):
+    want = build_neighbours(E, k, rows=rows)
+    bad = np.flatnonzero((got[rows] != want).any(axis=1))
+    assert bad.size == 0, f"{bad.size} of {len(rows)} rows differ; first row {rows[bad[0]]}: " \
+                          f"got {got[rows[bad[0]]][:12]} want {want[bad[0]][:12]}"
+
+
+def test_knn_tiny_full():
+    cfg = CONFIGS[1]
+    E = make_codebook(cfg)
+    got = run_knn(E, cfg.k)
+    _check_rows(E, cfg.k, got, np.arange(cfg.V))
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_knn_full_size_sampled_rows(idx):
+    cfg = CONFIGS[idx]
+    E = make_codebook(cfg)
+    got = run_knn(E, cfg.k)
+    assert np.array_equal(got[:, 0], np.arange(cfg.V))
+    assert got.min() >= 0 and got.max() < cfg.V
+    # every row is a set of k distinct codes
+    srt = np.sort(got, axis=1)
+    assert np.all(srt[:, 1:] != srt[:, :-1])
+    rows = np.random.default_rng(idx).choice(cfg.V, size=192, replace=False)
+    rows = np.concatenate([[0, cfg.V - 1], rows])
+    _check_rows(E, cfg.k, got, rows)
+
+
+def test_knn_ragged_shapes():
+    g = np.random.default_rng(0)
+    for V, D, k in [(1000, 6, 33), (77, 3, 77), (130, 20, 1), (4100, 50, 500), (65, 256, 64)]:
+        E = g.standard_normal((V, D))
+        E = (E / np.linalg.norm(E, axis=1, keepdims=True)).astype(np.float32)
+        got = run_knn(E, k)
+        _check_rows(E, k, got, np.arange(V))
+
+
+def test_knn_ties_and_duplicates_take_the_exact_path():
+    # exactly-unit rows with many exact ties, duplicated 12 times: > k + 1024 codes tie
+    rows = [np.array(s) * 0.5 for s in itertools.product([-1, 1], repeat=4)]
+    rows += [s * np.eye(4)[i] for i in range(4) for s in (1, -1)]
+    E = np.tile(np.array(rows, dtype=np.float32), (120, 1))          # V = 2880
+    got = run_knn(E, 40)
+    _check_rows(E, 40, got, np.arange(0, E.shape[0], 7))
+    E1 = np.tile(np.array([[0.6, 0.8]], dtype=np.float32), (1500, 1))  # all codes identical
+    got = run_knn(E1, 1300)
+    _check_rows(E1, 1300, got, np.arange(0, 1500, 31))
+
+
+def test_knn_unnormalised_rows_still_exact():
+    g = np.random.default_rng(1)
+    E = (g.standard_normal((900, 8)) * g.uniform(0.2, 3.0, size=(900, 1))).astype(np.float32)
+    got = run_knn(E, 100)
+    _check_rows(E, 100, got, np.arange(900))
+
+
+def test_knn_deterministic_and_errors():
+    cfg = CONFIGS[1]
+    E = make_codebook(cfg)
+    assert np.array_equal(run_knn(E, 16), run_knn(E, 16))
+    assert lpp.lpp_build_neighbours_workspace(1024, 8, 2000) == 0       # k > V
+    assert lpp.lpp_build_neighbours_workspace(1024, 300, 16) == 0       # D unsupported
