@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Tree-verify step throughput on one MI355X.
+
+One step = one lpp_tree_attention call (one layer) + one lpp_relaxed_verify call
+for the whole batch, on synthetic inputs shaped like the LlamaGen-XXL workload
+(workload config 3; see workloads/configs.py).  Inputs are resident in HBM before
+the timed region; R replicas of the input set are rotated so that consecutive
+steps do not find their inputs in the 256 MB last-level cache.
+
+Prints ONE JSON line (rank 0 / the only process).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def algorithmic_bytes(cfg, n_parents):
+    """Bytes one step has to move (each needed input read once, outputs written once)."""
+    e = 2 if cfg.kv_dtype == "bf16" else 4
+    B, H, M, S, Dh, V, k, N = cfg.B, cfg.H, cfg.M, cfg.S, cfg.Dh, cfg.V, cfg.k, cfg.N
+    attn = 2 * B * H * S * Dh * e + 3 * B * H * M * Dh * e + 4 * B * H * M * Dh
+    verify = 4 * B * V * (M + n_parents) + 4 * B * N * k
+    return attn, verify
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--config", type=int, default=3, help="workload config 1..5 (3 = the metric's shape)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-rotate", action="store_true", help="one replica only (cache-resident inputs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 "
+              "(the path shards by batch item with no exchange, nothing to measure across GPUs)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2502_06352_amd as lpp
+    from workloads import (CONFIGS, static_tree, children_lists, make_codebook,
+                           make_attention_inputs, make_verify_inputs)
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    lpp.lib()                                     # fails loudly if liblpp.so is not built
+
+    cfg = CONFIGS[args.config]
+    parent = static_tree(cfg.branching, cfg.N)
+    kids = children_lists(parent)
+    n_parents = sum(1 for c in kids if c)
+    tree = lpp.Tree(parent)
+    B, H, M, S, Dh, V, k = cfg.B, cfg.H, cfg.M, cfg.S, cfg.Dh, cfg.V, cfg.k
+    depth = max(tree.depth, 1)
+
+    # ---- inputs (CPU, seeded) -> HBM
+    E = make_codebook(cfg)
+    att = make_attention_inputs(cfg)
+    ver = make_verify_inputs(cfg, parent, rho=0.8)
+
+    def up(x):
+        return torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+
+    def up_bf16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    dE = up(E)
+    neigh = torch.empty((V, k), dtype=torch.int32, device=dev)
+    knn_ws = torch.empty(lpp.lpp_build_neighbours_workspace(V, cfg.D, k), dtype=torch.uint8, device=dev)
+    lpp.lpp_build_neighbours(dE, k, neigh, knn_ws)         # warm-up / result used below
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    knn_reps = 3
+    ev[0].record()
+    for _ in range(knn_reps):
+        lpp.lpp_build_neighbours(dE, k, neigh, knn_ws)
+    ev[1].record()
+    torch.cuda.synchronize()
+    knn_ms = ev[0].elapsed_time(ev[1]) / knn_reps
+    del knn_ws
+
+    attn_bytes, verify_bytes = algorithmic_bytes(cfg, n_parents)
+    step_bytes = attn_bytes + verify_bytes
+    R = 1 if args.no_rotate else max(2, int(np.ceil(512e6 / step_bytes)))
+    R = min(R, 64)
+    reps = []
+    for r in range(R):
+        d = {}
+        if cfg.kv_dtype == "bf16":
+            for n in ("q", "kc", "vc", "kt", "vt"):
+                d[n] = up_bf16(att[n + "_bits"])
+        else:
+            for n in ("q", "kc", "vc", "kt", "vt"):
+                d[n] = up(att[n])
+        for n in ("target_logits", "drafter_logits", "tokens", "u_accept", "u_final"):
+            d[n] = up(ver[n])
+        d["out_attn"] = torch.empty((B, H, M, Dh), dtype=torch.float32, device=dev)
+        d["vout"] = {"accept_len": torch.empty((B,), dtype=torch.int32, device=dev),
+                     "path": torch.empty((B, depth), dtype=torch.int32, device=dev),
+                     "final_token": torch.empty((B,), dtype=torch.int32, device=dev),
+                     "decision": torch.empty((B, M), dtype=torch.uint8, device=dev),
+                     "ratio": torch.empty((B, M), dtype=torch.float32, device=dev)}
+        reps.append(d)
+    attn_ws = torch.empty(max(256, lpp.lpp_tree_attention_workspace(tree, B, H, S, Dh)), dtype=torch.uint8, device=dev)
+    ver_ws = torch.empty(lpp.lpp_relaxed_verify_workspace(tree, B, V, k), dtype=torch.uint8, device=dev)
+    dtype = lpp.LPP_BF16 if cfg.kv_dtype == "bf16" else lpp.LPP_F32
+    stream = torch.cuda.current_stream()
+
+    def attention(d):
+        lpp.lpp_tree_attention(tree, dtype, d["q"], d["kc"], d["vc"], d["kt"], d["vt"], None,
+                               B, H, S, Dh, 0.0, d["out_attn"], attn_ws, stream)
+
+    def verify(d):
+        lpp.lpp_relaxed_verify(tree, d["target_logits"], d["drafter_logits"], cfg.ldv, cfg.vocab_offset, V, B,
+                               d["tokens"], neigh, k, k, cfg.lam, d["u_accept"], d["u_final"], d["vout"],
+                               ver_ws, stream)
+
+    def step(i):
+        d = reps[i % R]
+        attention(d)
+        verify(d)
+
+    # ---- timed region: W warm-up steps, then exactly K steps between synchronisations
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    steps_per_s = 1e3 / ms_per_step
+    mean_accept = float(torch.stack([d["vout"]["accept_len"] for d in reps]).float().mean().item())
+
+    # ---- per-call device time over the same K steps (HIP events on the launch stream)
+    def device_ms(fn):
+        ev[0].record()
+        for i in range(args.steps):
+            fn(reps[i % R])
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / args.steps
+
+    attn_ms = device_ms(attention)
+    verify_ms = device_ms(verify)
+    kern = {"tree_attention": {"ms": attn_ms, "bytes": attn_bytes, "GBs": attn_bytes / attn_ms / 1e6},
+            "relaxed_verify": {"ms": verify_ms, "bytes": verify_bytes, "GBs": verify_bytes / verify_ms / 1e6}}
+    dom = max(kern, key=lambda n: kern[n]["ms"])
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": kern[dom]["GBs"] / HBM_PEAK_GBS, "traffic": None,
+                "per_call": {n: {"ms": round(v["ms"], 5), "algorithmic_bytes": v["bytes"],
+                                 "GBs": round(v["GBs"], 1), "frac": round(v["GBs"] / HBM_PEAK_GBS, 4)}
+                             for n, v in kern.items()},
+                "step_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    knn_flops = 2.0 * 2.0 * V * V * cfg.D       # the contraction is swept twice
+    knn = {"ms": knn_ms, "mfma_dtype": "f32", "contraction_TFLOPs": knn_flops / (knn_ms * 1e-3) / 1e12,
+           "frac_of_fp32_mfma_peak": knn_flops / (knn_ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS,
+           "note": "one-time per codebook; whole build incl. select, float64 re-rank and sort"}
+
+    # ---- CPU baseline: the float64 numpy oracle, as it stands, on this host
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import relaxed_verify, tree_attention
+        neigh_h = neigh.cpu().numpy()           # input table for the oracle's verify step
+        nb = min(B, 1 if cfg.idx >= 5 else B)
+        t0 = time.perf_counter()
+        tree_attention(att["q"][:nb], att["kc"][:nb], att["vc"][:nb], att["kt"][:nb], att["vt"][:nb], parent)
+        relaxed_verify(parent, ver["target_logits"][:nb], ver["drafter_logits"][:nb], cfg.vocab_offset, V,
+                       ver["tokens"][:nb], neigh_h, k, cfg.lam, ver["u_accept"][:nb], ver["u_final"][:nb])
+        dt = time.perf_counter() - t0
+        cpu = {"value": (nb / B) / dt, "unit": "steps/s", "cores": len(os.sched_getaffinity(0)),
+               "kind": "oracle", "sample": f"{nb} of {B} batch items of one step, scaled to a full step "
+               f"({dt:.2f} s of CPU work; numpy float64, BLAS threads as configured by the host)"}
+
+    out = {"metric": "tree_verify_steps_per_sec", "value": steps_per_s, "unit": "steps/s",
+           "verified_nodes_per_sec": steps_per_s * B * cfg.N,
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "dtype_note": "verify: f32; attention: %s inputs on MFMA, f32 softmax/accumulate" % cfg.kv_dtype,
+           "data": "synthetic",
+           "config": {"workload": f"config {cfg.idx} ({cfg.name}): B={B} H={H}x{Dh} S={S} M={M} V={V} k={k} "
+                                  f"lambda={cfg.lam}", "replicas_rotated": R, "mean_accept_len": mean_accept},
+           "roofline": roofline, "cpu_baseline": cpu, "knn_build": knn}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
