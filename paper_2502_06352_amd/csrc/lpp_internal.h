@@ -22,7 +22,12 @@ struct lpp_tree {
   int32_t* d_child_ptr = nullptr;  // [M + 1]
   int32_t* d_child_idx = nullptr;  // [max(N, 1)]
   uint64_t* d_anc = nullptr;       // [M * words]
+  // "last block done" tickets of the fused kernels: zero between calls.  Calls that
+  // share one handle must therefore be ordered on a stream.
+  int32_t* d_counters = nullptr;   // [2 * LPP_COUNTER_SLOTS]: verify, then attention
 };
+
+#define LPP_COUNTER_SLOTS 4096
 
 #define LPP_HIP_TRY(expr)                      \
   do {                                         \

@@ -71,6 +71,9 @@ extern "C" int32_t lpp_tree_create(const int32_t* parent_host, int32_t M, lpp_tr
   if (hipMalloc((void**)&t->d_child_ptr, b_ptr) != hipSuccess) return fail();
   if (hipMalloc((void**)&t->d_child_idx, b_idx) != hipSuccess) return fail();
   if (hipMalloc((void**)&t->d_anc, b_anc) != hipSuccess) return fail();
+  const size_t b_cnt = sizeof(int32_t) * 2 * LPP_COUNTER_SLOTS;
+  if (hipMalloc((void**)&t->d_counters, b_cnt) != hipSuccess) return fail();
+  if (hipMemset(t->d_counters, 0, b_cnt) != hipSuccess) return fail();
   if (hipMemcpy(t->d_child_ptr, t->child_ptr.data(), b_ptr, hipMemcpyHostToDevice) != hipSuccess) return fail();
   if (hipMemcpy(t->d_child_idx, t->child_idx.data(), b_idx, hipMemcpyHostToDevice) != hipSuccess) return fail();
   if (hipMemcpy(t->d_anc, t->anc.data(), b_anc, hipMemcpyHostToDevice) != hipSuccess) return fail();
@@ -83,6 +86,7 @@ extern "C" int32_t lpp_tree_destroy(lpp_tree* t) {
   if (t->d_child_ptr) (void)hipFree(t->d_child_ptr);
   if (t->d_child_idx) (void)hipFree(t->d_child_idx);
   if (t->d_anc) (void)hipFree(t->d_anc);
+  if (t->d_counters) (void)hipFree(t->d_counters);
   delete t;
   return LPP_OK;
 }
