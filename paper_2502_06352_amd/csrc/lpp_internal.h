@@ -16,6 +16,7 @@ struct lpp_tree {
   int32_t max_children = 0;
   int32_t words = 0;         // 64-bit words per ancestor bitmask
   std::vector<int32_t> parent, row_depth, child_ptr, child_idx;
+  std::vector<int32_t> heavy_first;  // rows by descending number of children (ties: ascending row)
   std::vector<uint64_t> anc; // [M * words]
   // device copies (null for a host-only handle)
   int device = -1;

@@ -1,5 +1,6 @@
 // Static draft-tree handle: validation, derived tables, device upload.
 // (paper Sec. 2.1 static tree drafting; App. A.2 ancestors-only mask)
+#include <algorithm>
 #include <new>
 
 #include "lpp_internal.h"
@@ -47,6 +48,10 @@ extern "C" int32_t lpp_tree_create(const int32_t* parent_host, int32_t M, lpp_tr
   }
   std::vector<int32_t> fill(t->child_ptr.begin(), t->child_ptr.end() - 1);
   for (int32_t i = 1; i < M; ++i) t->child_idx[fill[t->parent[i]]++] = i;  // ascending row index
+  t->heavy_first.resize(M);
+  for (int32_t i = 0; i < M; ++i) t->heavy_first[i] = i;
+  std::stable_sort(t->heavy_first.begin(), t->heavy_first.end(),
+                   [&](int32_t x, int32_t y) { return cnt[x] > cnt[y]; });
   for (int32_t i = 0; i < M; ++i) {
     uint64_t* row = &t->anc[(size_t)i * t->words];
     if (i > 0)

@@ -3,38 +3,52 @@
 // residual update, inverse-CDF draw, and the walk (paper Sec. 4; Sec. 2.2;
 // App. A.2 Eq. 1-2).
 //
-// One workgroup of 1024 lanes owns one tree row of one batch item.  The row's
-// target distribution r lives in LDS (unnormalised, with a running scale) and in
-// the registers of the lanes that loaded it; the drafter distribution p stays in
-// registers only.  The two logit rows are therefore read from HBM exactly once and
-// every later pass (gather, prefix scan, residual, CDF search) runs out of LDS and
-// registers.  The neighbour rows of the row's first children are fetched while the
-// logits are still in flight.  Rows are independent: each is evaluated for the
-// outcome "all earlier siblings were rejected", which needs no uniform.  The last
-// row of a batch item to finish chases the recorded decisions from the root.
+// One workgroup owns one tree row of one batch item.  The two logit rows are read
+// from HBM exactly once, with every load issued before the first use; the row's
+// current target distribution r lives in LDS (unnormalised, with a running scale
+// rs) and in the registers of the lanes that own its tokens, the drafter
+// distribution p in registers only.  Rows are independent: each is evaluated for
+// the outcome "all earlier siblings were rejected", which needs no uniform.
+//
+// Per child the critical path is two workgroup barriers:
+//   wave 0   gathers r at the k neighbours (16 slots per lane, nearest first),
+//            takes the prefix sums, finds the end of A, moves A's mass onto x^
+//   barrier
+//   all      read their tokens of r' back from LDS, form [r' rs - p]_+ in place,
+//            reduce its sum
+//   barrier
+// Barriers wait for LDS traffic only, so global stores stay in flight across
+// them.  Rows with the most children are given the lowest block indices: their
+// loads are issued first and the sibling chain of the heavy rows runs while the
+// rest of the grid is still waiting for HBM.  The last row of a batch item to
+// finish chases the recorded decisions from the root.
 #include <limits.h>
 #include <math.h>
-#include <stdlib.h>
+
+#include <algorithm>
 
 #include "lpp_internal.h"
 
 namespace {
 
-constexpr int kThreads = 1024;
-constexpr int kWaves = kThreads / 64;
-constexpr int kPre = 8;        // children per row whose neighbour lists are staged in LDS
-constexpr int kPreK = 1024;    // neighbour slots staged per child
+constexpr int kMaxStage = 8;       // neighbour lists of the first children kept in LDS
+constexpr int kSlotChunk = 1024;   // neighbour slots per pass of wave 0
+constexpr int kSPL = 16;           // ... 16 per lane
+constexpr float kLog2e = 1.44269504088896340736f;
 
-struct TreeTab {               // by-value kernel argument: read through the scalar cache
+struct TreeTab {               // by-value kernel argument
   uint16_t child_ptr[LPP_MAX_ROWS + 1];
   uint16_t child_idx[LPP_MAX_ROWS];
+  uint16_t order[LPP_MAX_ROWS];   // rows by descending number of children
 };
 
 struct VerifyArgs {
   const float* target;
   const float* drafter;
   int64_t ldv;
-  int32_t off, V, M, kstride, k, depth;
+  int32_t off, V, M, B, kstride, k, depth;
+  int32_t nstage;         // child lists staged in LDS (<= kMaxStage)
+  int32_t kpitch;         // uint16 slots per staged list (multiple of 16)
   float lambda;
   const int32_t* tokens;
   const int32_t* neigh;
@@ -53,7 +67,6 @@ struct VerifyArgs {
   int32_t* ws_decision;   // [B*M] always written: the walk reads these
   int32_t* ws_final;      // [B*M]
   int32_t* counters;      // [B] zero between calls, or null: walk runs as its own kernel
-  int32_t dbg;
 };
 
 // ---- wave64 primitives on DPP (row shifts, row broadcasts)
@@ -70,13 +83,26 @@ __device__ __forceinline__ float wave_inclusive_scan(float v) {
   v += dpp_or<0x143, 0xc>(0.f, v);   // row_bcast:31 into rows 2 and 3
   return v;
 }
+// Inclusive scan of non-negative values that is non-decreasing over the lanes.
+// The tree above adds in a different order per lane, so neighbouring results can
+// be out of order by a rounding; a running maximum puts them back in order.
+__device__ __forceinline__ float wave_monotone_scan(float v) {
+  v = wave_inclusive_scan(v);
+  v = fmaxf(v, dpp_or<0x111, 0xf>(0.f, v));
+  v = fmaxf(v, dpp_or<0x112, 0xf>(0.f, v));
+  v = fmaxf(v, dpp_or<0x114, 0xf>(0.f, v));
+  v = fmaxf(v, dpp_or<0x118, 0xf>(0.f, v));
+  v = fmaxf(v, dpp_or<0x142, 0xa>(0.f, v));
+  v = fmaxf(v, dpp_or<0x143, 0xc>(0.f, v));
+  return v;
+}
 __device__ __forceinline__ float wave_prev_lane(float v, float first) {   // lane i <- lane i-1
   return dpp_or<0x138, 0xf>(first, v);                                      // wave_shr:1
 }
-__device__ __forceinline__ float wave_sum(float v) {
-  v = wave_inclusive_scan(v);
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+__device__ __forceinline__ float lane_value(float v, int lane) {           // `lane` is wave-uniform
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
+__device__ __forceinline__ float wave_sum(float v) { return lane_value(wave_inclusive_scan(v), 63); }
 __device__ __forceinline__ float wave_max(float v) {
   const float ninf = -INFINITY;
   v = fmaxf(v, dpp_or<0x111, 0xf>(ninf, v));
@@ -85,14 +111,25 @@ __device__ __forceinline__ float wave_max(float v) {
   v = fmaxf(v, dpp_or<0x118, 0xf>(ninf, v));
   v = fmaxf(v, dpp_or<0x142, 0xa>(ninf, v));
   v = fmaxf(v, dpp_or<0x143, 0xc>(ninf, v));
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+  return lane_value(v, 63);
 }
 
-// exp(x) for x <= 0 through the hardware exp2; the argument is formed in two
-// pieces so that its rounding error stays below one ulp of the result.
-__device__ __forceinline__ float exp_neg(float x) {
-  const float hi = 1.44269502162933349609375f, lo = 1.925963033500011e-08f;   // log2(e) = hi + lo
-  return __builtin_amdgcn_exp2f(__builtin_fmaf(x, hi, x * lo));
+// Workgroup barrier that orders LDS traffic only: outstanding global loads and
+// stores of the wave are not waited for.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+
+// exp(x - m) as exp2(x * log2(e) + m2), m2 = -m * log2(e): one FMA and the hardware exp2.
+__device__ __forceinline__ float exp2_fma(float x, float m2) {
+  return __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, m2));
 }
 
 template <bool ALIGNED>
@@ -131,69 +168,115 @@ __device__ __forceinline__ void walk_item(const TreeTab& tt, const int* dec, con
   *final_token = fin[cur];
 }
 
-// NCH = float4 chunks per lane; a row holds at most NCH * 4096 tokens.  Lane `tid`
-// owns tokens 4*(tid + 1024*j) .. +3 for j < NCH.
-template <int NCH, bool ALIGNED>
-__global__ __launch_bounds__(kThreads) void verify_rows_kernel(VerifyArgs a, TreeTab tt) {
-  extern __shared__ float r_lds[];  // NCH * 4096 floats: current r, unnormalised
-  __shared__ uint16_t s_neigh[kPre * kPreK];
-  __shared__ float s_red[2][kWaves];
-  __shared__ float s_seg[NCH][kWaves];
-  __shared__ float s_wtot[kWaves];
-  __shared__ int s_vidx[kWaves];
-  __shared__ float s_vval[kWaves];
-  __shared__ int s_lastpos[kWaves];
+// Sum (max), in wave order, of one float per wave held in LDS; every wave
+// computes the same value the same way.
+template <int NW>
+__device__ __forceinline__ float combine_sum(const float* s_w, int lane) {
+  float x = lane < NW ? s_w[lane] : 0.f;
+  x += dpp_or<0x111, 0xf>(0.f, x);
+  x += dpp_or<0x112, 0xf>(0.f, x);
+  x += dpp_or<0x114, 0xf>(0.f, x);
+  x += dpp_or<0x118, 0xf>(0.f, x);
+  return lane_value(x, NW - 1);
+}
+template <int NW>
+__device__ __forceinline__ float combine_max(const float* s_w, int lane) {
+  float x = lane < NW ? s_w[lane] : -INFINITY;
+  x = fmaxf(x, dpp_or<0x111, 0xf>(-INFINITY, x));
+  x = fmaxf(x, dpp_or<0x112, 0xf>(-INFINITY, x));
+  x = fmaxf(x, dpp_or<0x114, 0xf>(-INFINITY, x));
+  x = fmaxf(x, dpp_or<0x118, 0xf>(-INFINITY, x));
+  return lane_value(x, NW - 1);
+}
+
+// The 16 neighbour slots [base + 16 lane, +16) of token t's list, from global memory.
+__device__ __forceinline__ void load_slots_global(const int32_t* nrow, int base, int lane, int k, int V, int t,
+                                                  int (&n)[kSPL]) {
+#pragma unroll
+  for (int j = 0; j < kSPL; ++j) {
+    const int slot = base + kSPL * lane + j;
+    int x = t;
+    if (slot >= 1 && slot < k) x = min(max(nrow[slot], 0), V - 1);
+    n[j] = x;
+  }
+}
+
+// NT lanes per block, NCH float4 chunks per lane: a row holds at most NT * NCH * 4
+// tokens.  Lane `tid` owns tokens 4*(tid + NT*j) .. +3 for j < NCH.  In token order
+// the row is therefore a sequence of NCH * NW cells of 256 tokens, cell j * NW + w
+// owned by wave w.
+template <int NT, int NCH, bool ALIGNED>
+__global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab tt) {
+  constexpr int NW = NT / 64;
+  constexpr int NC = NCH * NW;             // cells
+  constexpr int CPL = (NC + 63) / 64;      // cells per lane of wave 0 in the final draw
+  constexpr int SPT = kSlotChunk / NT;     // slots per lane when a list is staged
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* r_lds = reinterpret_cast<float*>(smem);                              // NT * NCH * 4: current r
+  uint16_t* s_neigh = reinterpret_cast<uint16_t*>(r_lds + NT * NCH * 4);      // [nstage][kpitch]
+  __shared__ float s_max[2][NW];
+  __shared__ float s_sum[2][NW];
+  __shared__ float s_z[2][NW];
+  __shared__ float s_cell[64 * CPL];
   __shared__ int s_tok[LPP_MAX_ROWS];
   __shared__ float s_dlog[LPP_MAX_ROWS];
-  __shared__ int s_walk[2 * LPP_MAX_ROWS];
-  __shared__ int s_ticket;
+  __shared__ float s_u[LPP_MAX_ROWS];
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int P = blockIdx.x % a.M, b = blockIdx.x / a.M;
-  const int V = a.V;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int b = blockIdx.x % a.B;
+  const int P = tt.order[blockIdx.x / a.B];
+  const int V = a.V, k = a.k;
   const int64_t nodebase = (int64_t)b * a.M;
   const int64_t rowoff = (nodebase + P) * a.ldv + a.off;
   const float* trow = a.target + rowoff;
   const int cp0 = tt.child_ptr[P];
-  const int nchild = tt.child_ptr[P + 1] - cp0;
+  const int nchild = tt.child_ptr[P + 1] - cp0;      // < LPP_MAX_ROWS <= NT
   const float* drow = nchild > 0 ? a.drafter + rowoff : nullptr;
-  const int npre = min(nchild, kPre);
-  const int kpre = min(a.k, kPreK);
+  const int nst = min(nchild, a.nstage);
+  const int kst = min(k, kSlotChunk);                // slots of a staged list
 
-  // ---- small dependent reads first, so that they are not queued behind the rows
+  // ---- small reads that head a dependent chain go first
   int my_tok = 0;
-  float my_dlog = 0.f;
+  float my_u = 0.f;
   if (tid < nchild) {
-    my_tok = a.tokens[nodebase + tt.child_idx[cp0 + tid]];
-    my_tok = min(max(my_tok, 0), V - 1);
-    my_dlog = drow[my_tok];
+    const int c = tt.child_idx[cp0 + tid];
+    my_tok = a.tokens[nodebase + c];
+    my_u = a.u_accept[nodebase + c];
   }
-  int ptok[kPre];
+  int stok[kMaxStage];
 #pragma unroll
-  for (int ci = 0; ci < kPre; ++ci) {
-    ptok[ci] = 0;
-    if (ci < npre) {
-      const int t = a.tokens[nodebase + tt.child_idx[cp0 + ci]];
-      ptok[ci] = min(max(t, 0), V - 1);
-    }
+  for (int ci = 0; ci < kMaxStage; ++ci) {
+    stok[ci] = 0;
+    if (ci < nst) stok[ci] = a.tokens[nodebase + tt.child_idx[cp0 + ci]];
   }
+  const float u_fin = a.u_final[nodebase + P];
 
-  // ---- every HBM read of the row is issued up front
+  // ---- every HBM read of the two rows is issued up front
   float4 tv[NCH], dv[NCH];
 #pragma unroll
-  for (int j = 0; j < NCH; ++j) tv[j] = load_logits4<ALIGNED>(trow, 4 * (tid + kThreads * j), V);
+  for (int j = 0; j < NCH; ++j) tv[j] = load_logits4<ALIGNED>(trow, 4 * (tid + NT * j), V);
   if (nchild > 0) {
 #pragma unroll
-    for (int j = 0; j < NCH; ++j) dv[j] = load_logits4<ALIGNED>(drow, 4 * (tid + kThreads * j), V);
+    for (int j = 0; j < NCH; ++j) dv[j] = load_logits4<ALIGNED>(drow, 4 * (tid + NT * j), V);
   } else {
 #pragma unroll
     for (int j = 0; j < NCH; ++j) dv[j] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
   }
-  int nreg[kPre];
+  // ---- second link of the chain: drafter logit at the drafted token, neighbour lists
+  my_tok = min(max(my_tok, 0), V - 1);
+  float my_dlog = 0.f;
+  if (tid < nchild) my_dlog = drow[my_tok];
+  int nreg[kMaxStage][SPT];
 #pragma unroll
-  for (int ci = 0; ci < kPre; ++ci) {
-    nreg[ci] = ptok[ci];
-    if (ci < npre && tid > 0 && tid < kpre) nreg[ci] = a.neigh[(int64_t)ptok[ci] * a.kstride + tid];
+  for (int ci = 0; ci < kMaxStage; ++ci) {
+    const int t = min(max(stok[ci], 0), V - 1);
+#pragma unroll
+    for (int s = 0; s < SPT; ++s) {
+      const int i = tid + NT * s;
+      nreg[ci][s] = t;
+      if (ci < nst && i >= 1 && i < kst) nreg[ci][s] = a.neigh[(int64_t)t * a.kstride + i];
+    }
   }
 
   // ---- softmax statistics of both rows (Sec. 2 notation: q target, p drafter; T = 1)
@@ -205,39 +288,44 @@ __global__ __launch_bounds__(kThreads) void verify_rows_kernel(VerifyArgs a, Tre
   }
   mt = wave_max(mt);
   md = wave_max(md);
-  if (lane == 0) { s_red[0][w] = mt; s_red[1][w] = md; }
-  if (tid < nchild) { s_tok[tid] = my_tok; s_dlog[tid] = my_dlog; }
-  __syncthreads();
-  mt = s_red[0][0]; md = s_red[1][0];
-#pragma unroll
-  for (int i = 1; i < kWaves; ++i) { mt = fmaxf(mt, s_red[0][i]); md = fmaxf(md, s_red[1][i]); }
+  if (lane == 0) { s_max[0][w] = mt; s_max[1][w] = md; }
+  lds_barrier();
+  mt = combine_max<NW>(s_max[0], lane);
+  md = combine_max<NW>(s_max[1], lane);
   if (mt == -INFINITY) mt = 0.f;
   if (md == -INFINITY) md = 0.f;
-  __syncthreads();
+  const float mt2 = -mt * kLog2e, md2 = -md * kLog2e;   // exp(x - m) = exp2(x*log2e - m*log2e)
 
   float r_reg[NCH][4], p_reg[NCH][4];
   float st = 0.f, sd = 0.f;
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    r_reg[j][0] = exp_neg(tv[j].x - mt); r_reg[j][1] = exp_neg(tv[j].y - mt);
-    r_reg[j][2] = exp_neg(tv[j].z - mt); r_reg[j][3] = exp_neg(tv[j].w - mt);
-    p_reg[j][0] = exp_neg(dv[j].x - md); p_reg[j][1] = exp_neg(dv[j].y - md);
-    p_reg[j][2] = exp_neg(dv[j].z - md); p_reg[j][3] = exp_neg(dv[j].w - md);
+    r_reg[j][0] = exp2_fma(tv[j].x, mt2); r_reg[j][1] = exp2_fma(tv[j].y, mt2);
+    r_reg[j][2] = exp2_fma(tv[j].z, mt2); r_reg[j][3] = exp2_fma(tv[j].w, mt2);
+    p_reg[j][0] = exp2_fma(dv[j].x, md2); p_reg[j][1] = exp2_fma(dv[j].y, md2);
+    p_reg[j][2] = exp2_fma(dv[j].z, md2); p_reg[j][3] = exp2_fma(dv[j].w, md2);
     st += (r_reg[j][0] + r_reg[j][1]) + (r_reg[j][2] + r_reg[j][3]);
     sd += (p_reg[j][0] + p_reg[j][1]) + (p_reg[j][2] + p_reg[j][3]);
-    *reinterpret_cast<float4*>(&r_lds[4 * (tid + kThreads * j)]) =
+    *reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]) =
         make_float4(r_reg[j][0], r_reg[j][1], r_reg[j][2], r_reg[j][3]);
   }
-#pragma unroll
-  for (int ci = 0; ci < kPre; ++ci)
-    if (ci < npre) s_neigh[ci * kPreK + tid] = (uint16_t)min(max(nreg[ci], 0), V - 1);
   st = wave_sum(st);
   sd = wave_sum(sd);
-  if (lane == 0) { s_red[0][w] = st; s_red[1][w] = sd; }
-  __syncthreads();
-  st = 0.f; sd = 0.f;
+  if (lane == 0) { s_sum[0][w] = st; s_sum[1][w] = sd; }
+  // what wave 0 needs per child: token, drafter logit, uniform, neighbour list (16-bit indices)
+  if (tid < nchild) { s_tok[tid] = my_tok; s_dlog[tid] = my_dlog; s_u[tid] = my_u; }
 #pragma unroll
-  for (int i = 0; i < kWaves; ++i) { st += s_red[0][i]; sd += s_red[1][i]; }
+  for (int ci = 0; ci < kMaxStage; ++ci)
+    if (ci < nst) {
+#pragma unroll
+      for (int s = 0; s < SPT; ++s) {
+        const int i = tid + NT * s;
+        if (i < a.kpitch) s_neigh[ci * a.kpitch + i] = (uint16_t)min(max(nreg[ci][s], 0), V - 1);
+      }
+    }
+  lds_barrier();
+  st = combine_sum<NW>(s_sum[0], lane);
+  sd = combine_sum<NW>(s_sum[1], lane);
   float rs = st > 0.f ? 1.0f / st : 0.f;           // r_true = r_lds * rs
   const float inv_sd = sd > 0.f ? 1.0f / sd : 0.f;
 #pragma unroll
@@ -255,194 +343,228 @@ __global__ __launch_bounds__(kThreads) void verify_rows_kernel(VerifyArgs a, Tre
     if (a.p_tok) a.p_tok[nodebase] = 0.f;
   }
 
-  if (a.dbg == 1) { if (tid == 0) a.ws_final[nodebase + P] = (int)(rs * 1e6f + p_reg[0][0]); return; }
   // ---- children in static order, each against the current residual r
-  for (int ci = 0; ci < (a.dbg == 2 ? 0 : nchild); ++ci) {
-    const int c = tt.child_idx[cp0 + ci];
-    const int t = s_tok[ci];
-    const float rt = r_lds[t];
-    const float cap = a.lambda * rt;                 // bound: sum_A r < lambda * r(x^)   (Sec. 4)
-    const int32_t* nrow = a.neigh + (int64_t)t * a.kstride;
-    const bool staged = ci < kPre;
-    float carry = 0.f, mass_u = 0.f;
-    int jstar = INT_MAX;
-    int n_first = t;
-    for (int base = 0; base < a.k; base += kThreads) {
-      const int i = base + tid;
-      int n = t;
-      float v = 0.f;
-      if (i < a.k) {
-        if (i > 0) {
-          if (staged && base == 0) n = s_neigh[ci * kPreK + tid];
-          else { n = nrow[i]; n = min(max(n, 0), V - 1); }
+  for (int ci = 0; ci < nchild; ++ci) {
+    if (w == 0) {
+      const int c = tt.child_idx[cp0 + ci];
+      const int t = s_tok[ci];
+      const float rt = r_lds[t];
+      const float cap = a.lambda * rt;               // bound: sum_A r < lambda * r(x^)   (Sec. 4)
+      const int32_t* nrow = a.neigh + (int64_t)t * a.kstride;
+      const bool staged = ci < nst;
+
+      // A = longest nearest-first prefix whose running sum stays below the cap.  Lane L holds
+      // slots [16 L, 16 L + 16) of a pass; sums are taken slot by slot inside a lane and by a
+      // monotone scan across lanes, so "below the cap" switches off at most once.
+      int n0[kSPL];          // slots of the first pass (kept for the scatter)
+      float cb = 0.f;        // sum over the passes already taken
+      int jstar = -1;
+      float mass_u = 0.f;
+      for (int base = 0; base < k && jstar < 0; base += kSlotChunk) {
+        int n[kSPL];
+        if (base == 0 && staged) {
+          const uint4* src = reinterpret_cast<const uint4*>(s_neigh + ci * a.kpitch + kSPL * lane);
+          uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
+          if (kSPL * lane < a.kpitch) { lo = src[0]; hi = src[1]; }
+          const uint32_t wd[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+          for (int j = 0; j < kSPL; ++j) n[j] = (int)((wd[j >> 1] >> (16 * (j & 1))) & 0xFFFFu);
+        } else {
+          load_slots_global(nrow, base, lane, k, V, t, n);
         }
-        v = r_lds[n];
-      }
-      if (base == 0) n_first = n;
-      const float incl = wave_inclusive_scan(v);
-      if (lane == 63) s_wtot[w] = incl;
-      __syncthreads();
-      float prefix = carry, total = carry;
+        float cs[kSPL];
+        float run = 0.f;
 #pragma unroll
-      for (int ww = 0; ww < kWaves; ++ww) {
-        if (ww == w) prefix = total;
-        total += s_wtot[ww];
-      }
-      const float C = prefix + incl;                          // prefix sum including slot i
-      const float excl = prefix + wave_prev_lane(incl, 0.f);  // = C of slot i-1
-      const bool stop = (i >= 1 && i < a.k && !(C < cap)) || (i == a.k);
-      const unsigned long long bal = __ballot(stop);
-      if (bal) {
-        const int fl = __ffsll((long long)bal) - 1;
-        if (lane == fl) { s_vidx[w] = i; s_vval[w] = excl; }
-      } else if (lane == 0) {
-        s_vidx[w] = INT_MAX;
-      }
-      __syncthreads();
+        for (int j = 0; j < kSPL; ++j) {
+          const int slot = base + kSPL * lane + j;
+          if (slot == 0) n[j] = t;                   // x^ itself is always the first member
+          const float v = slot < k ? r_lds[n[j]] : 0.f;
+          run += v;
+          cs[j] = run;
+          if (base == 0) n0[j] = n[j];
+        }
+        const float incl = wave_monotone_scan(run);
+        const float excl = cb + wave_prev_lane(incl, 0.f);      // sum before my first slot
+        const float inclc = cb + incl;
+        const unsigned long long over = __ballot(!(inclc < cap));
+        if (over) {
+          const int lb = __builtin_amdgcn_readfirstlane(__ffsll((long long)over) - 1);
+          // in the boundary lane: first slot (other than slot 0) whose running sum reaches the cap
+          int myj = base + kSPL * lane + kSPL;
+          float mym = excl + cs[kSPL - 1];
 #pragma unroll
-      for (int ww = kWaves - 1; ww >= 0; --ww)
-        if (s_vidx[ww] != INT_MAX) { jstar = s_vidx[ww]; mass_u = s_vval[ww]; }
-      if (jstar != INT_MAX) break;
-      carry = total;
-    }
-    if (jstar == INT_MAX) { jstar = a.k; mass_u = carry; }
-
-    if (tid == 0) {
-      const float qt = rt * rs, m = mass_u * rs;
-      const float pt = exp_neg(s_dlog[ci] - md) * inv_sd;
-      const float u = a.u_accept[nodebase + c];
-      const int dec = (u * pt < m) ? 1 : 0;                   // u < min(1, mass / p(x^))
-      a.ws_decision[nodebase + c] = dec;
-      if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
-      if (a.ratio) a.ratio[nodebase + c] = m / pt;
-      if (a.mass) a.mass[nodebase + c] = m;
-      if (a.n_agg) a.n_agg[nodebase + c] = jstar;
-      if (a.q_tok) a.q_tok[nodebase + c] = qt;
-      if (a.p_tok) a.p_tok[nodebase + c] = pt;
-    }
-
-    // outcome "rejected": move A's mass onto x^ ...
-    for (int base = 0; base < jstar; base += kThreads) {
-      const int i = base + tid;
-      if (i >= 1 && i < jstar) {
-        int n = n_first;
-        if (base > 0) { n = nrow[i]; n = min(max(n, 0), V - 1); }
-        if (n != t) r_lds[n] = 0.f;
+          for (int j = kSPL - 1; j >= 0; --j) {
+            const int slot = base + kSPL * lane + j;
+            if (slot >= 1 && !(excl + cs[j] < cap)) { myj = slot; mym = j > 0 ? excl + cs[j - 1] : excl; }
+          }
+          jstar = min(__builtin_amdgcn_readlane(myj, lb), k);
+          mass_u = lane_value(mym, lb);
+        } else {
+          cb = lane_value(inclc, 63);
+        }
       }
+      if (jstar < 0) { jstar = k; mass_u = cb; }
+
+      if (lane == 0) {
+        const float qt = rt * rs, m = mass_u * rs;
+        const float pt = exp2_fma(s_dlog[ci], md2) * inv_sd;
+        const int dec = (s_u[ci] * pt < m) ? 1 : 0;             // u < min(1, mass / p(x^))
+        a.ws_decision[nodebase + c] = dec;
+        if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
+        if (a.ratio) a.ratio[nodebase + c] = m / pt;
+        if (a.mass) a.mass[nodebase + c] = m;
+        if (a.n_agg) a.n_agg[nodebase + c] = jstar;
+        if (a.q_tok) a.q_tok[nodebase + c] = qt;
+        if (a.p_tok) a.p_tok[nodebase + c] = pt;
+      }
+
+      // outcome "rejected": move A's mass onto x^ ...
+#pragma unroll
+      for (int j = 0; j < kSPL; ++j) {
+        const int slot = kSPL * lane + j;
+        if (slot >= 1 && slot < jstar && n0[j] != t) r_lds[n0[j]] = 0.f;
+      }
+      for (int base = kSlotChunk; base < jstar; base += kSlotChunk) {
+        int n[kSPL];
+        load_slots_global(nrow, base, lane, k, V, t, n);
+#pragma unroll
+        for (int j = 0; j < kSPL; ++j) {
+          const int slot = base + kSPL * lane + j;
+          if (slot < jstar && n[j] != t) r_lds[n[j]] = 0.f;
+        }
+      }
+      wave_lds_sync();
+      if (lane == 0) r_lds[t] = mass_u;
     }
-    if (tid == 0) r_lds[t] = mass_u;
-    __syncthreads();
-    // ... and keep the normalised positive part of (r' - p)    (Eq. 2)
+    lds_barrier();
+    // ... and keep the positive part of (r' - p); its sum is the new normaliser   (Eq. 2).
+    // Product and difference are rounded separately: a drafter equal to the target then
+    // leaves exactly nothing.
     float res[NCH][4];
     float z = 0.f;
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
-      const float4 rv = *reinterpret_cast<const float4*>(&r_lds[4 * (tid + kThreads * j)]);
+      float4* own = reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]);
+      const float4 rv = *own;
       res[j][0] = fmaxf(rv.x * rs - p_reg[j][0], 0.f);
       res[j][1] = fmaxf(rv.y * rs - p_reg[j][1], 0.f);
       res[j][2] = fmaxf(rv.z * rs - p_reg[j][2], 0.f);
       res[j][3] = fmaxf(rv.w * rs - p_reg[j][3], 0.f);
       z += (res[j][0] + res[j][1]) + (res[j][2] + res[j][3]);
+      *own = make_float4(res[j][0], res[j][1], res[j][2], res[j][3]);
     }
     z = wave_sum(z);
-    if (lane == 0) s_red[0][w] = z;
-    __syncthreads();
-    z = 0.f;
-#pragma unroll
-    for (int i = 0; i < kWaves; ++i) z += s_red[0][i];
+    if (lane == 0) s_z[ci & 1][w] = z;
+    lds_barrier();
+    z = combine_sum<NW>(s_z[ci & 1], lane);
     if (z > 0.f) {
       rs = 1.0f / z;
 #pragma unroll
-      for (int j = 0; j < NCH; ++j) {
+      for (int j = 0; j < NCH; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e) r_reg[j][e] = res[j][e];
-        *reinterpret_cast<float4*>(&r_lds[4 * (tid + kThreads * j)]) =
-            make_float4(res[j][0], res[j][1], res[j][2], res[j][3]);
-      }
-    } else {  // r' == p: nothing left to resample from; r stays as it was
+    } else {  // r' == p: nothing left to resample from; r stays as it was before this child
 #pragma unroll
       for (int j = 0; j < NCH; ++j)
-        *reinterpret_cast<float4*>(&r_lds[4 * (tid + kThreads * j)]) =
+        *reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]) =
             make_float4(r_reg[j][0], r_reg[j][1], r_reg[j][2], r_reg[j][3]);
+      lds_barrier();
     }
-    __syncthreads();
   }
 
-  // ---- draw from the final r by inverse CDF over ascending token index.  The
-  // cumulative sum is taken segment by segment (segment j = tokens [4096 j, 4096 j + 4096)),
-  // inside a segment chunk by chunk in lane order: the same sums decide which
-  // segment, which chunk and which token holds the target.
-  float csum[NCH], incl[NCH];
-  int lastpos = -1;
+  // ---- draw from the final r by inverse CDF over ascending token index: cell sums by
+  // their owners, then wave 0 finds the cell, the lane and the token.
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    csum[j] = (r_reg[j][0] + r_reg[j][1]) + (r_reg[j][2] + r_reg[j][3]);
-    incl[j] = wave_inclusive_scan(csum[j]);
-    if (lane == 63) s_seg[j][w] = incl[j];
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (r_reg[j][e] > 0.f) lastpos = 4 * (tid + kThreads * j) + e;
+    const float cs = (r_reg[j][0] + r_reg[j][1]) + (r_reg[j][2] + r_reg[j][3]);
+    const float tot = wave_sum(cs);
+    if (lane == 0) s_cell[j * NW + w] = tot;
   }
+  for (int i = NC + tid; i < 64 * CPL; i += NT) s_cell[i] = 0.f;
+  lds_barrier();
+  if (w != 0) return;
+
+  float cpre[CPL];           // running sum over my cells
+  {
+    float run = 0.f;
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, o));
-  if (lane == 0) s_lastpos[w] = lastpos;
-  __syncthreads();
-  float total = 0.f;
+    for (int i = 0; i < CPL; ++i) { run += s_cell[CPL * lane + i]; cpre[i] = run; }
+  }
+  const float cincl = wave_monotone_scan(cpre[CPL - 1]);
+  const float cexcl = wave_prev_lane(cincl, 0.f);
+  const float total = lane_value(cincl, 63);
+  const float target = u_fin * total;
+  // first cell whose cumulative sum exceeds the target, else the last cell with mass
+  int cellid = -1;
+  float cellbase = 0.f;
+  bool exact = true;
+  {
+    int myc = -1;
+    float myb = 0.f;
 #pragma unroll
-  for (int j = 0; j < NCH; ++j)
+    for (int i = CPL - 1; i >= 0; --i)
+      if (cexcl + cpre[i] > target) { myc = CPL * lane + i; myb = i > 0 ? cexcl + cpre[i - 1] : cexcl; }
+    const unsigned long long hit = __ballot(myc >= 0);
+    if (hit) {
+      const int l = __builtin_amdgcn_readfirstlane(__ffsll((long long)hit) - 1);
+      cellid = __builtin_amdgcn_readlane(myc, l);
+      cellbase = lane_value(myb, l);
+    } else {
+      exact = false;
+      int lastc = -1;
 #pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) total += s_seg[j][ww];
-  const float target = a.u_final[nodebase + P] * total;
-  // replay the same running sum: the lane whose chunk crosses the target reports it
-  float run = 0.f;
-  int found = INT_MAX;
-#pragma unroll
-  for (int j = 0; j < NCH; ++j) {
-    float prefix = run;
-#pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) {
-      if (ww == w) prefix = run;
-      run += s_seg[j][ww];
-    }
-    const float cin = prefix + incl[j];                          // cumulative mass after my chunk
-    const float cex = prefix + wave_prev_lane(incl[j], 0.f);     // ... and before it
-    if (found == INT_MAX && cin > target) {
-      const float u0 = cex + r_reg[j][0], u1 = u0 + r_reg[j][1], u2 = u1 + r_reg[j][2];
-      int e = u0 > target ? 0 : u1 > target ? 1 : u2 > target ? 2 : 3;
-      if (!(r_reg[j][e] > 0.f)) e = r_reg[j][3] > 0.f ? 3 : r_reg[j][2] > 0.f ? 2 : r_reg[j][1] > 0.f ? 1 : 0;
-      found = 4 * (tid + kThreads * j) + e;
+      for (int i = 0; i < CPL; ++i)
+        if (s_cell[CPL * lane + i] > 0.f) lastc = CPL * lane + i;
+      const unsigned long long any = __ballot(lastc >= 0);
+      if (any) cellid = __builtin_amdgcn_readlane(lastc, __builtin_amdgcn_readfirstlane(63 - __builtin_clzll(any)));
     }
   }
-  // lowest token over the block: chunks are ordered by (segment, wave, lane) = token order
-  int best = found;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) best = min(best, __shfl_xor(best, o));
-  if (lane == 0) s_vidx[w] = best;
-  __syncthreads();
-  if (tid == 0) {
-    int x = INT_MAX, lp = -1;
-    for (int ww = 0; ww < kWaves; ++ww) { x = min(x, s_vidx[ww]); lp = max(lp, s_lastpos[ww]); }
-    if (x == INT_MAX) x = lp >= 0 ? lp : 0;
-    x = min(x, V - 1);
+  int x = 0;
+  if (cellid >= 0) {
+    const int tb = 4 * (64 * (cellid % NW) + NT * (cellid / NW));      // first token of the cell
+    const float4 rv = *reinterpret_cast<const float4*>(&r_lds[tb + 4 * lane]);
+    const float cs = (rv.x + rv.y) + (rv.z + rv.w);
+    const float incl = wave_monotone_scan(cs);
+    const float lbase = cellbase + wave_prev_lane(incl, 0.f);
+    const unsigned long long hit = exact ? __ballot(cellbase + incl > target) : 0ull;
+    int l;
+    if (hit) {
+      l = __ffsll((long long)hit) - 1;
+    } else {
+      const unsigned long long any = __ballot(cs > 0.f);
+      l = any ? 63 - __builtin_clzll(any) : 0;
+    }
+    l = __builtin_amdgcn_readfirstlane(l);
+    const float u0 = lbase + rv.x, u1 = u0 + rv.y, u2 = u1 + rv.z;
+    int e = 3;
+    if (hit) e = u0 > target ? 0 : u1 > target ? 1 : u2 > target ? 2 : 3;
+    const float pick = e == 0 ? rv.x : e == 1 ? rv.y : e == 2 ? rv.z : rv.w;
+    if (!(pick > 0.f)) e = rv.w > 0.f ? 3 : rv.z > 0.f ? 2 : rv.y > 0.f ? 1 : 0;
+    x = __builtin_amdgcn_readlane(tb + 4 * lane + e, l);
+  }
+  x = min(x, V - 1);
+  int ticket = 0;
+  if (lane == 0) {
     a.ws_final[nodebase + P] = x;
     if (a.final_all) a.final_all[nodebase + P] = x;
     if (a.counters) {
       __threadfence();
-      s_ticket = atomicAdd(&a.counters[b], 1);
+      ticket = atomicAdd(&a.counters[b], 1);
     }
   }
   if (!a.counters) return;
-  __syncthreads();
-  if (s_ticket != a.M - 1) return;
+  ticket = __builtin_amdgcn_readfirstlane(ticket);
+  if (ticket != a.M - 1) return;
   // ---- this row finished last for item b: every decision of the item is visible
   __threadfence();
-  if (tid < a.M) {
-    s_walk[tid] = __hip_atomic_load(&a.ws_decision[nodebase + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_walk[LPP_MAX_ROWS + tid] = __hip_atomic_load(&a.ws_final[nodebase + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  int* s_walk = reinterpret_cast<int*>(smem);     // r is dead: [0, M) decisions, [M, 2M) draws
+  for (int i = lane; i < a.M; i += 64) {
+    s_walk[i] = __hip_atomic_load(&a.ws_decision[nodebase + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_walk[a.M + i] = __hip_atomic_load(&a.ws_final[nodebase + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  __syncthreads();
-  if (tid == 0) {
-    walk_item(tt, s_walk, s_walk + LPP_MAX_ROWS, a.depth, a.accept_len + b, a.path + (int64_t)b * a.depth,
+  wave_lds_sync();
+  if (lane == 0) {
+    walk_item(tt, s_walk, s_walk + a.M, a.depth, a.accept_len + b, a.path + (int64_t)b * a.depth,
               a.final_token + b);
     a.counters[b] = 0;    // ready for the next call
   }
@@ -456,17 +578,17 @@ __global__ void walk_kernel(VerifyArgs a, TreeTab tt, int B) {
             a.path + (int64_t)b * a.depth, a.final_token + b);
 }
 
-template <int NCH, bool ALIGNED>
-int32_t launch_rows(const VerifyArgs& a, const TreeTab& tt, int B, hipStream_t stream) {
-  static bool attr_set = false;
-  const size_t lds = (size_t)NCH * 4096 * sizeof(float);
-  auto kern = verify_rows_kernel<NCH, ALIGNED>;
-  if (!attr_set) {
+template <int NT, int NCH, bool ALIGNED>
+int32_t launch_rows(const VerifyArgs& a, const TreeTab& tt, hipStream_t stream) {
+  static size_t attr_lds = 0;   // largest dynamic LDS size this instantiation was enabled for
+  const size_t lds = (size_t)NT * NCH * 4 * sizeof(float) + (size_t)a.nstage * a.kpitch * sizeof(uint16_t);
+  auto kern = verify_rows_kernel<NT, NCH, ALIGNED>;
+  if (lds > attr_lds) {
     LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
+    attr_lds = lds;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)(B * a.M)), dim3(kThreads), lds, stream, a, tt);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.M)), dim3(NT), lds, stream, a, tt);
   LPP_HIP_TRY(hipGetLastError());
   return LPP_OK;
 }
@@ -500,8 +622,10 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
 
   VerifyArgs a;
   a.target = target_logits; a.drafter = drafter_logits; a.ldv = ldv; a.off = vocab_offset;
-  a.V = V; a.M = tree->M; a.kstride = kstride; a.k = k; a.lambda = lambda;
+  a.V = V; a.M = tree->M; a.B = B; a.kstride = kstride; a.k = k; a.lambda = lambda;
   a.depth = tree->depth > 0 ? tree->depth : 1;
+  a.nstage = std::min<int32_t>(tree->max_children, kMaxStage);
+  a.kpitch = (int32_t)lpp_align_up((size_t)std::min<int32_t>(k, kSlotChunk), 16);
   a.tokens = tokens; a.neigh = neigh; a.u_accept = u_accept; a.u_final = u_final;
   a.decision = out->decision; a.ratio = out->ratio; a.mass = out->mass; a.n_agg = out->n_agg;
   a.q_tok = out->q_tok; a.p_tok = out->p_tok; a.final_all = out->final_tok_all;
@@ -512,28 +636,26 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
                                           lpp_align_up(nodes * sizeof(int32_t), 256));
   const bool fused_walk = B <= LPP_COUNTER_SLOTS;
   a.counters = fused_walk ? tree->d_counters : nullptr;
-  { const char* e = getenv("LPP_DBG"); a.dbg = e ? atoi(e) : 0; }
 
   TreeTab tt;
   for (int i = 0; i <= LPP_MAX_ROWS; ++i)
     tt.child_ptr[i] = (uint16_t)(i <= tree->M ? tree->child_ptr[i] : tree->child_ptr[tree->M]);
   for (int i = 0; i < LPP_MAX_ROWS; ++i)
     tt.child_idx[i] = (uint16_t)(i < tree->M - 1 ? tree->child_idx[i] : 0);
+  for (int i = 0; i < LPP_MAX_ROWS; ++i) tt.order[i] = (uint16_t)(i < tree->M ? tree->heavy_first[i] : 0);
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   auto aligned16 = [&](const float* p) {
     return p == nullptr || ((reinterpret_cast<uintptr_t>(p + vocab_offset) % 16 == 0) && (ldv % 4 == 0));
   };
   const bool al = aligned16(target_logits) && aligned16(drafter_logits);
-  const int nch = V <= 4096 ? 1 : V <= 8192 ? 2 : V <= 16384 ? 4 : 8;
   int32_t st;
-#define LPP_DISPATCH(N) st = al ? launch_rows<N, true>(a, tt, B, s) : launch_rows<N, false>(a, tt, B, s)
-  switch (nch) {
-    case 1: LPP_DISPATCH(1); break;
-    case 2: LPP_DISPATCH(2); break;
-    case 4: LPP_DISPATCH(4); break;
-    default: LPP_DISPATCH(8); break;
-  }
+#define LPP_DISPATCH(T, N) st = al ? launch_rows<T, N, true>(a, tt, s) : launch_rows<T, N, false>(a, tt, s)
+  if (V <= 2048) LPP_DISPATCH(512, 1);
+  else if (V <= 4096) LPP_DISPATCH(512, 2);
+  else if (V <= 8192) LPP_DISPATCH(512, 4);
+  else if (V <= 16384) LPP_DISPATCH(512, 8);
+  else LPP_DISPATCH(1024, 8);
 #undef LPP_DISPATCH
   if (st != LPP_OK) return st;
   if (!fused_walk) {
