@@ -14,6 +14,7 @@ struct lpp_tree {
   int32_t depth = 0;         // levels below the root
   int32_t n_parents = 0;     // rows with at least one child
   int32_t max_children = 0;
+  bool consecutive_children = true;  // the children of every row are consecutive rows
   int32_t words = 0;         // 64-bit words per ancestor bitmask
   std::vector<int32_t> parent, row_depth, child_ptr, child_idx;
   std::vector<int32_t> heavy_first;  // rows by descending number of children (ties: ascending row)

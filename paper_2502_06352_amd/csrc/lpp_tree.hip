@@ -48,6 +48,9 @@ extern "C" int32_t lpp_tree_create(const int32_t* parent_host, int32_t M, lpp_tr
   }
   std::vector<int32_t> fill(t->child_ptr.begin(), t->child_ptr.end() - 1);
   for (int32_t i = 1; i < M; ++i) t->child_idx[fill[t->parent[i]]++] = i;  // ascending row index
+  for (int32_t i = 0; i < M; ++i)
+    for (int32_t ci = t->child_ptr[i] + 1; ci < t->child_ptr[i + 1]; ++ci)
+      if (t->child_idx[ci] != t->child_idx[ci - 1] + 1) t->consecutive_children = false;
   t->heavy_first.resize(M);
   for (int32_t i = 0; i < M; ++i) t->heavy_first[i] = i;
   std::stable_sort(t->heavy_first.begin(), t->heavy_first.end(),

@@ -36,10 +36,22 @@ constexpr int kSlotChunk = 1024;   // neighbour slots per pass of wave 0
 constexpr int kSPL = 16;           // ... 16 per lane
 constexpr float kLog2e = 1.44269504088896340736f;
 
-struct TreeTab {               // by-value kernel argument
-  uint16_t child_ptr[LPP_MAX_ROWS + 1];
-  uint16_t child_idx[LPP_MAX_ROWS];
-  uint16_t order[LPP_MAX_ROWS];   // rows by descending number of children
+// Build with -DLPP_VERIFY_TIMESTAMPS to record per-block phase times (100 MHz counter)
+// behind the workspace the caller passes; off in the product build.
+#ifdef LPP_VERIFY_TIMESTAMPS
+#define LPP_TS(i)                                                                                   \
+  do {                                                                                              \
+    if (threadIdx.x == 0) a.ts[(int64_t)blockIdx.x * 32 + (i)] = __builtin_amdgcn_s_memrealtime(); \
+  } while (0)
+#else
+#define LPP_TS(i) do { } while (0)
+#endif
+
+// By-value kernel argument, indexed by a wave-uniform value only (scalar loads).  Entry i
+// describes the row handled by blocks [i B, (i+1) B): rows are sorted by descending number of
+// children.  row | nchild << 8 | first child row << 16 | offset into child_idx << 24.
+struct TreeTab {
+  uint32_t rowinfo[LPP_MAX_ROWS];
 };
 
 struct VerifyArgs {
@@ -67,6 +79,11 @@ struct VerifyArgs {
   int32_t* ws_decision;   // [B*M] always written: the walk reads these
   int32_t* ws_final;      // [B*M]
   int32_t* counters;      // [B] zero between calls, or null: walk runs as its own kernel
+  const int32_t* child_idx;   // [N] children of all rows, grouped by parent (read only if !consecutive)
+  int32_t consecutive;    // every row's children are consecutive rows
+#ifdef LPP_VERIFY_TIMESTAMPS
+  unsigned long long* ts; // [blocks][32]
+#endif
 };
 
 // ---- wave64 primitives on DPP (row shifts, row broadcasts)
@@ -149,23 +166,47 @@ __device__ __forceinline__ float4 load_logits4(const float* row, int e0, int V) 
 }
 
 // Follow the first accepted child per level from the root (App. A.2: accepted
-// tokens are kept, everything after the first rejection is discarded).
-__device__ __forceinline__ void walk_item(const TreeTab& tt, const int* dec, const int* fin, int depth,
-                                          int32_t* accept_len, int32_t* path, int32_t* final_token) {
-  int cur = 0, n = 0;
-  while (n < depth) {
-    int nxt = -1;
-    for (int ci = tt.child_ptr[cur]; ci < tt.child_ptr[cur + 1]; ++ci) {
-      const int c = tt.child_idx[ci];
-      if (dec[c]) { nxt = c; break; }
+// tokens are kept, everything after the first rejection is discarded).  One wave.
+// word[i] = parent(i) << 1 | decision(i) as the row kernels recorded it; s_next is M ints
+// of LDS, s_fin another M.  Children are tried in ascending row index, so the child a
+// row hands over to is the lowest accepted one.
+__device__ __forceinline__ void walk_wave(const int32_t* word, const int32_t* fin, int M, int depth, int lane,
+                                          int* s_next, int* s_fin, int32_t* accept_len, int32_t* path,
+                                          int32_t* final_token) {
+  int wd[LPP_MAX_ROWS / 64];
+#pragma unroll
+  for (int q = 0; q < LPP_MAX_ROWS / 64; ++q) {
+    const int i = lane + 64 * q;
+    wd[q] = 0;
+    if (i < M) {
+      wd[q] = __hip_atomic_load(&word[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_fin[i] = __hip_atomic_load(&fin[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_next[i] = INT_MAX;
     }
-    if (nxt < 0) break;
-    path[n++] = nxt;
-    cur = nxt;
   }
-  for (int i = n; i < depth; ++i) path[i] = -1;
-  *accept_len = n;
-  *final_token = fin[cur];
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+#pragma unroll
+  for (int q = 0; q < LPP_MAX_ROWS / 64; ++q) {
+    const int i = lane + 64 * q;
+    if (i >= 1 && i < M && (wd[q] & 1)) atomicMin(&s_next[wd[q] >> 1], i);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+  if (lane == 0) {
+    int cur = 0, n = 0;
+    while (n < depth) {
+      const int nxt = s_next[cur];
+      if (nxt == INT_MAX) break;
+      path[n++] = nxt;
+      cur = nxt;
+    }
+    for (int i = n; i < depth; ++i) path[i] = -1;
+    *accept_len = n;
+    *final_token = s_fin[cur];
+  }
 }
 
 // Sum (max), in wave order, of one float per wave held in LDS; every wave
@@ -189,15 +230,18 @@ __device__ __forceinline__ float combine_max(const float* s_w, int lane) {
   return lane_value(x, NW - 1);
 }
 
-// The 16 neighbour slots [base + 16 lane, +16) of token t's list, from global memory.
+// The 16 neighbour slots [base + 16 lane, +16) of token t's list, from global memory
+// (lists that are not staged in LDS: more than kMaxStage children, or k > kSlotChunk).
+// Every load is in bounds and unconditional, so that the 16 of them overlap.
 __device__ __forceinline__ void load_slots_global(const int32_t* nrow, int base, int lane, int k, int V, int t,
                                                   int (&n)[kSPL]) {
+  int raw[kSPL];
+#pragma unroll
+  for (int j = 0; j < kSPL; ++j) raw[j] = nrow[min(base + kSPL * lane + j, k - 1)];
 #pragma unroll
   for (int j = 0; j < kSPL; ++j) {
     const int slot = base + kSPL * lane + j;
-    int x = t;
-    if (slot >= 1 && slot < k) x = min(max(nrow[slot], 0), V - 1);
-    n[j] = x;
+    n[j] = (slot >= 1 && slot < k) ? min(max(raw[j], 0), V - 1) : t;
   }
 }
 
@@ -219,36 +263,39 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   __shared__ float s_z[2][NW];
   __shared__ float s_cell[64 * CPL];
   __shared__ int s_tok[LPP_MAX_ROWS];
+  __shared__ int s_child[LPP_MAX_ROWS];
   __shared__ float s_dlog[LPP_MAX_ROWS];
   __shared__ float s_u[LPP_MAX_ROWS];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  LPP_TS(0);
   const int b = blockIdx.x % a.B;
-  const int P = tt.order[blockIdx.x / a.B];
+  const uint32_t ri = tt.rowinfo[blockIdx.x / a.B];
+  const int P = ri & 255u;
   const int V = a.V, k = a.k;
   const int64_t nodebase = (int64_t)b * a.M;
   const int64_t rowoff = (nodebase + P) * a.ldv + a.off;
   const float* trow = a.target + rowoff;
-  const int cp0 = tt.child_ptr[P];
-  const int nchild = tt.child_ptr[P + 1] - cp0;      // < LPP_MAX_ROWS <= NT
+  const int nchild = (ri >> 8) & 255u;               // < LPP_MAX_ROWS <= NT
+  const int first_child = (ri >> 16) & 255u, cp0 = ri >> 24;
   const float* drow = nchild > 0 ? a.drafter + rowoff : nullptr;
   const int nst = min(nchild, a.nstage);
   const int kst = min(k, kSlotChunk);                // slots of a staged list
 
   // ---- small reads that head a dependent chain go first
-  int my_tok = 0;
+  int my_tok = 0, my_child = 0;
   float my_u = 0.f;
   if (tid < nchild) {
-    const int c = tt.child_idx[cp0 + tid];
-    my_tok = a.tokens[nodebase + c];
-    my_u = a.u_accept[nodebase + c];
+    my_child = a.consecutive ? first_child + tid : a.child_idx[cp0 + tid];
+    my_tok = a.tokens[nodebase + my_child];
+    my_u = a.u_accept[nodebase + my_child];
   }
   int stok[kMaxStage];
 #pragma unroll
   for (int ci = 0; ci < kMaxStage; ++ci) {
     stok[ci] = 0;
-    if (ci < nst) stok[ci] = a.tokens[nodebase + tt.child_idx[cp0 + ci]];
+    if (ci < nst) stok[ci] = a.tokens[nodebase + (a.consecutive ? first_child + ci : a.child_idx[cp0 + ci])];
   }
   const float u_fin = a.u_final[nodebase + P];
 
@@ -265,6 +312,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   }
   // ---- second link of the chain: drafter logit at the drafted token, neighbour lists
   my_tok = min(max(my_tok, 0), V - 1);
+  LPP_TS(1);
   float my_dlog = 0.f;
   if (tid < nchild) my_dlog = drow[my_tok];
   int nreg[kMaxStage][SPT];
@@ -272,10 +320,10 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   for (int ci = 0; ci < kMaxStage; ++ci) {
     const int t = min(max(stok[ci], 0), V - 1);
 #pragma unroll
-    for (int s = 0; s < SPT; ++s) {
-      const int i = tid + NT * s;
-      nreg[ci][s] = t;
-      if (ci < nst && i >= 1 && i < kst) nreg[ci][s] = a.neigh[(int64_t)t * a.kstride + i];
+    for (int s = 0; s < SPT; ++s) nreg[ci][s] = t;
+    if (ci < nst) {                                  // uniform
+#pragma unroll
+      for (int s = 0; s < SPT; ++s) nreg[ci][s] = a.neigh[(int64_t)t * a.kstride + min(tid + NT * s, kst - 1)];
     }
   }
 
@@ -286,6 +334,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     mt = fmaxf(mt, fmaxf(fmaxf(tv[j].x, tv[j].y), fmaxf(tv[j].z, tv[j].w)));
     md = fmaxf(md, fmaxf(fmaxf(dv[j].x, dv[j].y), fmaxf(dv[j].z, dv[j].w)));
   }
+  LPP_TS(2);
   mt = wave_max(mt);
   md = wave_max(md);
   if (lane == 0) { s_max[0][w] = mt; s_max[1][w] = md; }
@@ -313,7 +362,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   sd = wave_sum(sd);
   if (lane == 0) { s_sum[0][w] = st; s_sum[1][w] = sd; }
   // what wave 0 needs per child: token, drafter logit, uniform, neighbour list (16-bit indices)
-  if (tid < nchild) { s_tok[tid] = my_tok; s_dlog[tid] = my_dlog; s_u[tid] = my_u; }
+  if (tid < nchild) { s_tok[tid] = my_tok; s_child[tid] = my_child; s_dlog[tid] = my_dlog; s_u[tid] = my_u; }
 #pragma unroll
   for (int ci = 0; ci < kMaxStage; ++ci)
     if (ci < nst) {
@@ -324,6 +373,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       }
     }
   lds_barrier();
+  LPP_TS(3);
   st = combine_sum<NW>(s_sum[0], lane);
   sd = combine_sum<NW>(s_sum[1], lane);
   float rs = st > 0.f ? 1.0f / st : 0.f;           // r_true = r_lds * rs
@@ -346,7 +396,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   // ---- children in static order, each against the current residual r
   for (int ci = 0; ci < nchild; ++ci) {
     if (w == 0) {
-      const int c = tt.child_idx[cp0 + ci];
+      const int c = s_child[ci];
       const int t = s_tok[ci];
       const float rt = r_lds[t];
       const float cap = a.lambda * rt;               // bound: sum_A r < lambda * r(x^)   (Sec. 4)
@@ -409,7 +459,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
         const float qt = rt * rs, m = mass_u * rs;
         const float pt = exp2_fma(s_dlog[ci], md2) * inv_sd;
         const int dec = (s_u[ci] * pt < m) ? 1 : 0;             // u < min(1, mass / p(x^))
-        a.ws_decision[nodebase + c] = dec;
+        a.ws_decision[nodebase + c] = (P << 1) | dec;        // what the walk needs of this node
         if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
         if (a.ratio) a.ratio[nodebase + c] = m / pt;
         if (a.mass) a.mass[nodebase + c] = m;
@@ -436,7 +486,9 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       wave_lds_sync();
       if (lane == 0) r_lds[t] = mass_u;
     }
+    if (ci < 8) LPP_TS(4 + 3 * ci);
     lds_barrier();
+    if (ci < 8) LPP_TS(5 + 3 * ci);
     // ... and keep the positive part of (r' - p); its sum is the new normaliser   (Eq. 2).
     // Product and difference are rounded separately: a drafter equal to the target then
     // leaves exactly nothing.
@@ -456,6 +508,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     z = wave_sum(z);
     if (lane == 0) s_z[ci & 1][w] = z;
     lds_barrier();
+    if (ci < 8) LPP_TS(6 + 3 * ci);
     z = combine_sum<NW>(s_z[ci & 1], lane);
     if (z > 0.f) {
       rs = 1.0f / z;
@@ -481,6 +534,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     if (lane == 0) s_cell[j * NW + w] = tot;
   }
   for (int i = NC + tid; i < 64 * CPL; i += NT) s_cell[i] = 0.f;
+  LPP_TS(28);
   lds_barrier();
   if (w != 0) return;
 
@@ -543,6 +597,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     x = __builtin_amdgcn_readlane(tb + 4 * lane + e, l);
   }
   x = min(x, V - 1);
+  LPP_TS(29);
   int ticket = 0;
   if (lane == 0) {
     a.ws_final[nodebase + P] = x;
@@ -557,25 +612,20 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   if (ticket != a.M - 1) return;
   // ---- this row finished last for item b: every decision of the item is visible
   __threadfence();
-  int* s_walk = reinterpret_cast<int*>(smem);     // r is dead: [0, M) decisions, [M, 2M) draws
-  for (int i = lane; i < a.M; i += 64) {
-    s_walk[i] = __hip_atomic_load(&a.ws_decision[nodebase + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_walk[a.M + i] = __hip_atomic_load(&a.ws_final[nodebase + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-  wave_lds_sync();
-  if (lane == 0) {
-    walk_item(tt, s_walk, s_walk + a.M, a.depth, a.accept_len + b, a.path + (int64_t)b * a.depth,
-              a.final_token + b);
-    a.counters[b] = 0;    // ready for the next call
-  }
+  int* s_walk = reinterpret_cast<int*>(smem);     // r is dead
+  walk_wave(a.ws_decision + nodebase, a.ws_final + nodebase, a.M, a.depth, lane, s_walk, s_walk + a.M,
+            a.accept_len + b, a.path + (int64_t)b * a.depth, a.final_token + b);
+  if (lane == 0) a.counters[b] = 0;    // ready for the next call
+  LPP_TS(30);
 }
 
-// Stand-alone walk for batches larger than the counter array.
-__global__ void walk_kernel(VerifyArgs a, TreeTab tt, int B) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B) return;
-  walk_item(tt, a.ws_decision + (int64_t)b * a.M, a.ws_final + (int64_t)b * a.M, a.depth, a.accept_len + b,
-            a.path + (int64_t)b * a.depth, a.final_token + b);
+// Stand-alone walk for batches larger than the counter array: one wave per item.
+__global__ __launch_bounds__(64) void walk_kernel(VerifyArgs a) {
+  __shared__ int s_walk[2 * LPP_MAX_ROWS];
+  const int b = blockIdx.x;
+  const int64_t nodebase = (int64_t)b * a.M;
+  walk_wave(a.ws_decision + nodebase, a.ws_final + nodebase, a.M, a.depth, threadIdx.x, s_walk, s_walk + a.M,
+            a.accept_len + b, a.path + (int64_t)b * a.depth, a.final_token + b);
 }
 
 template <int NT, int NCH, bool ALIGNED>
@@ -636,13 +686,23 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
                                           lpp_align_up(nodes * sizeof(int32_t), 256));
   const bool fused_walk = B <= LPP_COUNTER_SLOTS;
   a.counters = fused_walk ? tree->d_counters : nullptr;
+#ifdef LPP_VERIFY_TIMESTAMPS
+  a.ts = reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(ws) + need);
+#endif
 
+  a.child_idx = tree->d_child_idx;
+  a.consecutive = tree->consecutive_children ? 1 : 0;
   TreeTab tt;
-  for (int i = 0; i <= LPP_MAX_ROWS; ++i)
-    tt.child_ptr[i] = (uint16_t)(i <= tree->M ? tree->child_ptr[i] : tree->child_ptr[tree->M]);
-  for (int i = 0; i < LPP_MAX_ROWS; ++i)
-    tt.child_idx[i] = (uint16_t)(i < tree->M - 1 ? tree->child_idx[i] : 0);
-  for (int i = 0; i < LPP_MAX_ROWS; ++i) tt.order[i] = (uint16_t)(i < tree->M ? tree->heavy_first[i] : 0);
+  for (int i = 0; i < LPP_MAX_ROWS; ++i) {
+    uint32_t ri = 0;
+    if (i < tree->M) {
+      const int32_t row = tree->heavy_first[i];
+      const int32_t c0 = tree->child_ptr[row], nc = tree->child_ptr[row + 1] - c0;
+      const int32_t first = nc > 0 ? tree->child_idx[c0] : 0;
+      ri = (uint32_t)row | ((uint32_t)nc << 8) | ((uint32_t)first << 16) | ((uint32_t)(nc > 0 ? c0 : 0) << 24);
+    }
+    tt.rowinfo[i] = ri;
+  }
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   auto aligned16 = [&](const float* p) {
@@ -659,7 +719,7 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
 #undef LPP_DISPATCH
   if (st != LPP_OK) return st;
   if (!fused_walk) {
-    hipLaunchKernelGGL(walk_kernel, dim3((unsigned)((B + 63) / 64)), dim3(64), 0, s, a, tt, B);
+    hipLaunchKernelGGL(walk_kernel, dim3((unsigned)B), dim3(64), 0, s, a);
     LPP_HIP_TRY(hipGetLastError());
   }
   return LPP_OK;
