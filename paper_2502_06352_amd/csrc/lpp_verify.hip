@@ -10,18 +10,18 @@
 // distribution p in registers only.  Rows are independent: each is evaluated for
 // the outcome "all earlier siblings were rejected", which needs no uniform.
 //
-// Per child the critical path is two workgroup barriers:
-//   wave 0   gathers r at the k neighbours (16 slots per lane, nearest first),
-//            takes the prefix sums, finds the end of A, moves A's mass onto x^
+// Per child the critical path is three workgroup barriers:
+//   all      gather r at the child's k neighbours (two slots per lane, nearest first),
+//            scan the sums inside each wave
+//   barrier
+//   all      add the wave totals in order, find the end of A, move A's mass onto x^
 //   barrier
 //   all      read their tokens of r' back from LDS, form [r' rs - p]_+ in place,
 //            reduce its sum
 //   barrier
 // Barriers wait for LDS traffic only, so global stores stay in flight across
-// them.  Rows with the most children are given the lowest block indices: their
-// loads are issued first and the sibling chain of the heavy rows runs while the
-// rest of the grid is still waiting for HBM.  The last row of a batch item to
-// finish chases the recorded decisions from the root.
+// them.  Rows with the most children are given the lowest block indices.  The
+// last row of a batch item to finish follows the recorded decisions from the root.
 #include <limits.h>
 #include <math.h>
 
@@ -32,8 +32,6 @@
 namespace {
 
 constexpr int kMaxStage = 8;       // neighbour lists of the first children kept in LDS
-constexpr int kSlotChunk = 1024;   // neighbour slots per pass of wave 0
-constexpr int kSPL = 16;           // ... 16 per lane
 constexpr float kLog2e = 1.44269504088896340736f;
 
 // Build with -DLPP_VERIFY_TIMESTAMPS to record per-block phase times (100 MHz counter)
@@ -59,8 +57,7 @@ struct VerifyArgs {
   const float* drafter;
   int64_t ldv;
   int32_t off, V, M, B, kstride, k, depth;
-  int32_t nstage;         // child lists staged in LDS (<= kMaxStage)
-  int32_t kpitch;         // uint16 slots per staged list (multiple of 16)
+  int32_t nstage;         // child lists whose first pass is staged in LDS (<= kMaxStage)
   float lambda;
   const int32_t* tokens;
   const int32_t* neigh;
@@ -149,20 +146,28 @@ __device__ __forceinline__ float exp2_fma(float x, float m2) {
   return __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, m2));
 }
 
+// Four consecutive logits of a row, tokens e0 .. e0+3.  The load is unconditional and in
+// bounds (clamped address); mask_logits4 afterwards turns tokens at or past V into -inf.
+// The two are separate so that nothing consumes a load while others are still to be issued.
+// ALIGNED: 16-byte aligned rows and V % 4 == 0.
 template <bool ALIGNED>
 __device__ __forceinline__ float4 load_logits4(const float* row, int e0, int V) {
-  const float ninf = -INFINITY;
-  if (ALIGNED && e0 + 3 < V) {
+  if (ALIGNED) {
     typedef float vec4f __attribute__((ext_vector_type(4)));
-    const vec4f x = __builtin_nontemporal_load(reinterpret_cast<const vec4f*>(row + e0));
+    const vec4f x = __builtin_nontemporal_load(reinterpret_cast<const vec4f*>(row + min(e0, V - 4)));
     return make_float4(x.x, x.y, x.z, x.w);
   }
   float4 v;
-  v.x = (e0 + 0 < V) ? __builtin_nontemporal_load(row + e0 + 0) : ninf;
-  v.y = (e0 + 1 < V) ? __builtin_nontemporal_load(row + e0 + 1) : ninf;
-  v.z = (e0 + 2 < V) ? __builtin_nontemporal_load(row + e0 + 2) : ninf;
-  v.w = (e0 + 3 < V) ? __builtin_nontemporal_load(row + e0 + 3) : ninf;
+  v.x = __builtin_nontemporal_load(row + min(e0 + 0, V - 1));
+  v.y = __builtin_nontemporal_load(row + min(e0 + 1, V - 1));
+  v.z = __builtin_nontemporal_load(row + min(e0 + 2, V - 1));
+  v.w = __builtin_nontemporal_load(row + min(e0 + 3, V - 1));
   return v;
+}
+__device__ __forceinline__ float4 mask_logits4(float4 v, int e0, int V) {
+  const float ninf = -INFINITY;
+  return make_float4(e0 + 0 < V ? v.x : ninf, e0 + 1 < V ? v.y : ninf, e0 + 2 < V ? v.z : ninf,
+                     e0 + 3 < V ? v.w : ninf);
 }
 
 // Follow the first accepted child per level from the root (App. A.2: accepted
@@ -230,42 +235,33 @@ __device__ __forceinline__ float combine_max(const float* s_w, int lane) {
   return lane_value(x, NW - 1);
 }
 
-// The 16 neighbour slots [base + 16 lane, +16) of token t's list, from global memory
-// (lists that are not staged in LDS: more than kMaxStage children, or k > kSlotChunk).
-// Every load is in bounds and unconditional, so that the 16 of them overlap.
-__device__ __forceinline__ void load_slots_global(const int32_t* nrow, int base, int lane, int k, int V, int t,
-                                                  int (&n)[kSPL]) {
-  int raw[kSPL];
-#pragma unroll
-  for (int j = 0; j < kSPL; ++j) raw[j] = nrow[min(base + kSPL * lane + j, k - 1)];
-#pragma unroll
-  for (int j = 0; j < kSPL; ++j) {
-    const int slot = base + kSPL * lane + j;
-    n[j] = (slot >= 1 && slot < k) ? min(max(raw[j], 0), V - 1) : t;
-  }
-}
-
 // NT lanes per block, NCH float4 chunks per lane: a row holds at most NT * NCH * 4
 // tokens.  Lane `tid` owns tokens 4*(tid + NT*j) .. +3 for j < NCH.  In token order
 // the row is therefore a sequence of NCH * NW cells of 256 tokens, cell j * NW + w
-// owned by wave w.
+// owned by wave w.  The neighbour list of a child is taken in passes of 2 NT slots,
+// lane `tid` holding slots 2 tid and 2 tid + 1 of the pass.
 template <int NT, int NCH, bool ALIGNED>
 __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab tt) {
   constexpr int NW = NT / 64;
   constexpr int NC = NCH * NW;             // cells
   constexpr int CPL = (NC + 63) / 64;      // cells per lane of wave 0 in the final draw
-  constexpr int SPT = kSlotChunk / NT;     // slots per lane when a list is staged
+  constexpr int PASS = 2 * NT;             // neighbour slots per pass
+  constexpr int MAXP = (LPP_MAX_K + PASS - 1) / PASS;
+  constexpr int ZC = NT * NCH * 4;         // index of a cell of r_lds that always holds 0
   extern __shared__ __align__(16) unsigned char smem[];
-  float* r_lds = reinterpret_cast<float*>(smem);                              // NT * NCH * 4: current r
-  uint16_t* s_neigh = reinterpret_cast<uint16_t*>(r_lds + NT * NCH * 4);      // [nstage][kpitch]
+  float* r_lds = reinterpret_cast<float*>(smem);                              // current r, then the zero cell
+  uint32_t* s_neigh = reinterpret_cast<uint32_t*>(r_lds + ZC + 4);            // [nstage][NT] pairs of 16-bit slots
   __shared__ float s_max[2][NW];
   __shared__ float s_sum[2][NW];
   __shared__ float s_z[2][NW];
+  __shared__ float s_wtot[2][NW];
   __shared__ float s_cell[64 * CPL];
   __shared__ int s_tok[LPP_MAX_ROWS];
   __shared__ int s_child[LPP_MAX_ROWS];
   __shared__ float s_dlog[LPP_MAX_ROWS];
   __shared__ float s_u[LPP_MAX_ROWS];
+  __shared__ int s_jstar;
+  __shared__ float s_mass;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -281,25 +277,8 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   const int first_child = (ri >> 16) & 255u, cp0 = ri >> 24;
   const float* drow = nchild > 0 ? a.drafter + rowoff : nullptr;
   const int nst = min(nchild, a.nstage);
-  const int kst = min(k, kSlotChunk);                // slots of a staged list
 
-  // ---- small reads that head a dependent chain go first
-  int my_tok = 0, my_child = 0;
-  float my_u = 0.f;
-  if (tid < nchild) {
-    my_child = a.consecutive ? first_child + tid : a.child_idx[cp0 + tid];
-    my_tok = a.tokens[nodebase + my_child];
-    my_u = a.u_accept[nodebase + my_child];
-  }
-  int stok[kMaxStage];
-#pragma unroll
-  for (int ci = 0; ci < kMaxStage; ++ci) {
-    stok[ci] = 0;
-    if (ci < nst) stok[ci] = a.tokens[nodebase + (a.consecutive ? first_child + ci : a.child_idx[cp0 + ci])];
-  }
-  const float u_fin = a.u_final[nodebase + P];
-
-  // ---- every HBM read of the two rows is issued up front
+  // ---- every HBM read of the two rows is issued first: nothing else is as long
   float4 tv[NCH], dv[NCH];
 #pragma unroll
   for (int j = 0; j < NCH; ++j) tv[j] = load_logits4<ALIGNED>(trow, 4 * (tid + NT * j), V);
@@ -308,68 +287,95 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     for (int j = 0; j < NCH; ++j) dv[j] = load_logits4<ALIGNED>(drow, 4 * (tid + NT * j), V);
   } else {
 #pragma unroll
-    for (int j = 0; j < NCH; ++j) dv[j] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    for (int j = 0; j < NCH; ++j) dv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  // ---- second link of the chain: drafter logit at the drafted token, neighbour lists
-  my_tok = min(max(my_tok, 0), V - 1);
-  LPP_TS(1);
-  float my_dlog = 0.f;
-  if (tid < nchild) my_dlog = drow[my_tok];
-  int nreg[kMaxStage][SPT];
+  // ---- the chain row -> drafted tokens -> neighbour lists.  The tokens of the first
+  // children sit at wave-uniform addresses (scalar loads, which do not queue behind the rows).
+  const float u_fin = a.u_final[nodebase + P];
+  int crow[kMaxStage], stok[kMaxStage];
 #pragma unroll
   for (int ci = 0; ci < kMaxStage; ++ci) {
-    const int t = min(max(stok[ci], 0), V - 1);
-#pragma unroll
-    for (int s = 0; s < SPT; ++s) nreg[ci][s] = t;
-    if (ci < nst) {                                  // uniform
-#pragma unroll
-      for (int s = 0; s < SPT; ++s) nreg[ci][s] = a.neigh[(int64_t)t * a.kstride + min(tid + NT * s, kst - 1)];
-    }
+    crow[ci] = first_child + ci;
+    if (!a.consecutive && ci < nst) crow[ci] = a.child_idx[cp0 + ci];
   }
+#pragma unroll
+  for (int ci = 0; ci < kMaxStage; ++ci) {
+    stok[ci] = 0;
+    if (ci < nst) stok[ci] = min(max(a.tokens[nodebase + crow[ci]], 0), V - 1);
+  }
+  int my_tok = 0, my_child = 0;
+#pragma unroll
+  for (int ci = 0; ci < kMaxStage; ++ci)
+    if (tid == ci) { my_tok = stok[ci]; my_child = crow[ci]; }
+  if (nchild > kMaxStage && tid >= kMaxStage && tid < nchild) {     // rows with many children: a slower chain
+    my_child = a.consecutive ? first_child + tid : a.child_idx[cp0 + tid];
+    my_tok = min(max(a.tokens[nodebase + my_child], 0), V - 1);
+  }
+  float my_u = 0.f, my_dlog = 0.f;
+  if (tid < nchild) {
+    my_u = a.u_accept[nodebase + my_child];
+    my_dlog = drow[my_tok];
+  }
+  int nreg[kMaxStage][2];      // slots tid and tid + NT of the first pass (lists that are not
+#pragma unroll                 // staged re-read the first child's: no branch, no extra traffic)
+  for (int ci = 0; ci < kMaxStage; ++ci) {
+    const int32_t* nrow = a.neigh + (int64_t)(ci < nst ? stok[ci] : stok[0]) * a.kstride;
+    nreg[ci][0] = nrow[min(tid, k - 1)];
+    nreg[ci][1] = nrow[min(tid + NT, k - 1)];
+  }
+
+  __builtin_amdgcn_sched_barrier(0);   // every load above is issued before anything below waits
 
   // ---- softmax statistics of both rows (Sec. 2 notation: q target, p drafter; T = 1)
   float mt = -INFINITY, md = -INFINITY;
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
+    tv[j] = mask_logits4(tv[j], 4 * (tid + NT * j), V);
+    dv[j] = mask_logits4(dv[j], 4 * (tid + NT * j), nchild > 0 ? V : 0);
     mt = fmaxf(mt, fmaxf(fmaxf(tv[j].x, tv[j].y), fmaxf(tv[j].z, tv[j].w)));
     md = fmaxf(md, fmaxf(fmaxf(dv[j].x, dv[j].y), fmaxf(dv[j].z, dv[j].w)));
   }
-  LPP_TS(2);
   mt = wave_max(mt);
   md = wave_max(md);
   if (lane == 0) { s_max[0][w] = mt; s_max[1][w] = md; }
   lds_barrier();
+  LPP_TS(2);
   mt = combine_max<NW>(s_max[0], lane);
   md = combine_max<NW>(s_max[1], lane);
   if (mt == -INFINITY) mt = 0.f;
   if (md == -INFINITY) md = 0.f;
   const float mt2 = -mt * kLog2e, md2 = -md * kLog2e;   // exp(x - m) = exp2(x*log2e - m*log2e)
 
-  float r_reg[NCH][4], p_reg[NCH][4];
+  float p_reg[NCH][4];
   float st = 0.f, sd = 0.f;
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    r_reg[j][0] = exp2_fma(tv[j].x, mt2); r_reg[j][1] = exp2_fma(tv[j].y, mt2);
-    r_reg[j][2] = exp2_fma(tv[j].z, mt2); r_reg[j][3] = exp2_fma(tv[j].w, mt2);
+    const float r0 = exp2_fma(tv[j].x, mt2), r1 = exp2_fma(tv[j].y, mt2);
+    const float r2 = exp2_fma(tv[j].z, mt2), r3 = exp2_fma(tv[j].w, mt2);
     p_reg[j][0] = exp2_fma(dv[j].x, md2); p_reg[j][1] = exp2_fma(dv[j].y, md2);
     p_reg[j][2] = exp2_fma(dv[j].z, md2); p_reg[j][3] = exp2_fma(dv[j].w, md2);
-    st += (r_reg[j][0] + r_reg[j][1]) + (r_reg[j][2] + r_reg[j][3]);
+    st += (r0 + r1) + (r2 + r3);
     sd += (p_reg[j][0] + p_reg[j][1]) + (p_reg[j][2] + p_reg[j][3]);
-    *reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]) =
-        make_float4(r_reg[j][0], r_reg[j][1], r_reg[j][2], r_reg[j][3]);
+    *reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]) = make_float4(r0, r1, r2, r3);
   }
   st = wave_sum(st);
   sd = wave_sum(sd);
   if (lane == 0) { s_sum[0][w] = st; s_sum[1][w] = sd; }
-  // what wave 0 needs per child: token, drafter logit, uniform, neighbour list (16-bit indices)
+  if (tid == 0) r_lds[ZC] = 0.f;
+  // per child: token, row, drafter logit, uniform, and the first pass of its neighbour list
+  // as 16-bit indices into r_lds (slot 0 = x^ itself; slots past k point at the zero cell)
   if (tid < nchild) { s_tok[tid] = my_tok; s_child[tid] = my_child; s_dlog[tid] = my_dlog; s_u[tid] = my_u; }
 #pragma unroll
   for (int ci = 0; ci < kMaxStage; ++ci)
     if (ci < nst) {
+      uint16_t* dst = reinterpret_cast<uint16_t*>(s_neigh + ci * NT);
 #pragma unroll
-      for (int s = 0; s < SPT; ++s) {
-        const int i = tid + NT * s;
-        if (i < a.kpitch) s_neigh[ci * a.kpitch + i] = (uint16_t)min(max(nreg[ci][s], 0), V - 1);
+      for (int s = 0; s < 2; ++s) {
+        const int slot = tid + NT * s;
+        int n = min(max(nreg[ci][s], 0), V - 1);
+        if (slot == 0) n = stok[ci];
+        if (slot >= k) n = ZC;
+        dst[slot] = (uint16_t)n;
       }
     }
   lds_barrier();
@@ -394,116 +400,103 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   }
 
   // ---- children in static order, each against the current residual r
+  int tog = 0;
   for (int ci = 0; ci < nchild; ++ci) {
-    if (w == 0) {
-      const int c = s_child[ci];
-      const int t = s_tok[ci];
-      const float rt = r_lds[t];
-      const float cap = a.lambda * rt;               // bound: sum_A r < lambda * r(x^)   (Sec. 4)
-      const int32_t* nrow = a.neigh + (int64_t)t * a.kstride;
-      const bool staged = ci < nst;
+    const int t = s_tok[ci];
+    const float rt = r_lds[t];
+    const float cap = a.lambda * rt;                 // bound: sum_A r < lambda * r(x^)   (Sec. 4)
+    const int32_t* nrow = a.neigh + (int64_t)t * a.kstride;
 
-      // A = longest nearest-first prefix whose running sum stays below the cap.  Lane L holds
-      // slots [16 L, 16 L + 16) of a pass; sums are taken slot by slot inside a lane and by a
-      // monotone scan across lanes, so "below the cap" switches off at most once.
-      int n0[kSPL];          // slots of the first pass (kept for the scatter)
-      float cb = 0.f;        // sum over the passes already taken
-      int jstar = -1;
-      float mass_u = 0.f;
-      for (int base = 0; base < k && jstar < 0; base += kSlotChunk) {
-        int n[kSPL];
-        if (base == 0 && staged) {
-          const uint4* src = reinterpret_cast<const uint4*>(s_neigh + ci * a.kpitch + kSPL * lane);
-          uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
-          if (kSPL * lane < a.kpitch) { lo = src[0]; hi = src[1]; }
-          const uint32_t wd[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    // A = longest nearest-first prefix whose running sum stays below the cap.  G(i), the sum
+    // through the slots of lane i, is non-decreasing over the block by construction (monotone
+    // scan inside a wave, wave totals added one after the other), so the lanes wholly inside A,
+    // the one lane A ends in and the lanes outside follow each other in that order.
+    uint32_t pn[MAXP];       // my two slots of each pass (16-bit indices)
+    float pv0[MAXP], pv1[MAXP];
+    uint32_t pm[MAXP];       // bit 0 / 1: slot zeroed by me in this pass
+    float carry = 0.f;       // sum over the passes already taken
+    bool found = false;
 #pragma unroll
-          for (int j = 0; j < kSPL; ++j) n[j] = (int)((wd[j >> 1] >> (16 * (j & 1))) & 0xFFFFu);
+    for (int ps = 0; ps < MAXP; ++ps) {
+      pn[ps] = 0; pv0[ps] = pv1[ps] = 0.f; pm[ps] = 0;
+      if (ps * PASS < k && !found) {                 // uniform
+        const int sl0 = ps * PASS + 2 * tid;
+        uint32_t pk;
+        if (ps == 0 && ci < nst) {
+          pk = s_neigh[ci * NT + tid];
         } else {
-          load_slots_global(nrow, base, lane, k, V, t, n);
+          const int x0 = nrow[min(sl0, k - 1)], x1 = nrow[min(sl0 + 1, k - 1)];
+          int n0 = min(max(x0, 0), V - 1), n1 = min(max(x1, 0), V - 1);
+          if (sl0 == 0) n0 = t;
+          if (sl0 >= k) n0 = ZC;
+          if (sl0 + 1 >= k) n1 = ZC;
+          pk = (uint32_t)n0 | ((uint32_t)n1 << 16);
         }
-        float cs[kSPL];
-        float run = 0.f;
+        const int n0 = pk & 0xFFFFu, n1 = pk >> 16;
+        const float v0 = r_lds[n0], v1 = r_lds[n1];
+        const float incl = wave_monotone_scan(v0 + v1);
+        if (lane == 63) s_wtot[tog][w] = incl;
+        lds_barrier();
+        float base = carry, mybase = carry;
 #pragma unroll
-        for (int j = 0; j < kSPL; ++j) {
-          const int slot = base + kSPL * lane + j;
-          if (slot == 0) n[j] = t;                   // x^ itself is always the first member
-          const float v = slot < k ? r_lds[n[j]] : 0.f;
-          run += v;
-          cs[j] = run;
-          if (base == 0) n0[j] = n[j];
+        for (int i = 0; i < NW; ++i) {
+          if (i == w) mybase = base;
+          base += s_wtot[tog][i];
         }
-        const float incl = wave_monotone_scan(run);
-        const float excl = cb + wave_prev_lane(incl, 0.f);      // sum before my first slot
-        const float inclc = cb + incl;
-        const unsigned long long over = __ballot(!(inclc < cap));
-        if (over) {
-          const int lb = __builtin_amdgcn_readfirstlane(__ffsll((long long)over) - 1);
-          // in the boundary lane: first slot (other than slot 0) whose running sum reaches the cap
-          int myj = base + kSPL * lane + kSPL;
-          float mym = excl + cs[kSPL - 1];
-#pragma unroll
-          for (int j = kSPL - 1; j >= 0; --j) {
-            const int slot = base + kSPL * lane + j;
-            if (slot >= 1 && !(excl + cs[j] < cap)) { myj = slot; mym = j > 0 ? excl + cs[j - 1] : excl; }
-          }
-          jstar = min(__builtin_amdgcn_readlane(myj, lb), k);
-          mass_u = lane_value(mym, lb);
-        } else {
-          cb = lane_value(inclc, 63);
+        tog ^= 1;
+        const float G = mybase + incl;                         // through my slots
+        const float pc = mybase + wave_prev_lane(incl, 0.f);   // before my slots
+        const bool full = G < cap;
+        const bool edge = !full && (pc < cap || sl0 == 0);     // A ends in my slots
+        const float c0 = pc + v0;
+        const bool m0 = full || (edge && (sl0 == 0 || c0 < cap));
+        if (edge) {
+          s_jstar = min(m0 ? sl0 + 1 : sl0, k);
+          s_mass = m0 ? c0 : pc;
+          r_lds[t] = m0 ? c0 : pc;                             // A's mass moves onto x^ ...
         }
+        const bool z0 = m0 && sl0 != 0 && n0 != t, z1 = full && n1 != t;
+        if (z0) r_lds[n0] = 0.f;                               // ... and leaves the other members
+        if (z1) r_lds[n1] = 0.f;
+        pn[ps] = pk; pv0[ps] = v0; pv1[ps] = v1; pm[ps] = (z0 ? 1u : 0u) | (z1 ? 2u : 0u);
+        carry = base;
+        found = !(base < cap);
       }
-      if (jstar < 0) { jstar = k; mass_u = cb; }
-
-      if (lane == 0) {
-        const float qt = rt * rs, m = mass_u * rs;
-        const float pt = exp2_fma(s_dlog[ci], md2) * inv_sd;
-        const int dec = (s_u[ci] * pt < m) ? 1 : 0;             // u < min(1, mass / p(x^))
-        a.ws_decision[nodebase + c] = (P << 1) | dec;        // what the walk needs of this node
-        if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
-        if (a.ratio) a.ratio[nodebase + c] = m / pt;
-        if (a.mass) a.mass[nodebase + c] = m;
-        if (a.n_agg) a.n_agg[nodebase + c] = jstar;
-        if (a.q_tok) a.q_tok[nodebase + c] = qt;
-        if (a.p_tok) a.p_tok[nodebase + c] = pt;
-      }
-
-      // outcome "rejected": move A's mass onto x^ ...
-#pragma unroll
-      for (int j = 0; j < kSPL; ++j) {
-        const int slot = kSPL * lane + j;
-        if (slot >= 1 && slot < jstar && n0[j] != t) r_lds[n0[j]] = 0.f;
-      }
-      for (int base = kSlotChunk; base < jstar; base += kSlotChunk) {
-        int n[kSPL];
-        load_slots_global(nrow, base, lane, k, V, t, n);
-#pragma unroll
-        for (int j = 0; j < kSPL; ++j) {
-          const int slot = base + kSPL * lane + j;
-          if (slot < jstar && n[j] != t) r_lds[n[j]] = 0.f;
-        }
-      }
-      wave_lds_sync();
-      if (lane == 0) r_lds[t] = mass_u;
     }
+    if (!found && tid == 0) { s_jstar = k; s_mass = carry; r_lds[t] = carry; }
     if (ci < 8) LPP_TS(4 + 3 * ci);
     lds_barrier();
     if (ci < 8) LPP_TS(5 + 3 * ci);
-    // ... and keep the positive part of (r' - p); its sum is the new normaliser   (Eq. 2).
-    // Product and difference are rounded separately: a drafter equal to the target then
-    // leaves exactly nothing.
-    float res[NCH][4];
+    if (tid == 0) {
+      const int c = s_child[ci];
+      const int jstar = s_jstar;
+      const float qt = rt * rs, m = s_mass * rs;
+      const float pt = exp2_fma(s_dlog[ci], md2) * inv_sd;
+      const int dec = (s_u[ci] * pt < m) ? 1 : 0;               // u < min(1, mass / p(x^))
+      a.ws_decision[nodebase + c] = (P << 1) | dec;             // what the walk needs of this node
+      if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
+      if (a.ratio) a.ratio[nodebase + c] = m / pt;
+      if (a.mass) a.mass[nodebase + c] = m;
+      if (a.n_agg) a.n_agg[nodebase + c] = jstar;
+      if (a.q_tok) a.q_tok[nodebase + c] = qt;
+      if (a.p_tok) a.p_tok[nodebase + c] = pt;
+    }
+    // outcome "rejected": keep the positive part of (r' - p); its sum is the new normaliser
+    // (Eq. 2).  Product and difference are rounded separately: a drafter equal to the target
+    // then leaves exactly nothing.
+    float4 rv[NCH];
     float z = 0.f;
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
       float4* own = reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]);
-      const float4 rv = *own;
-      res[j][0] = fmaxf(rv.x * rs - p_reg[j][0], 0.f);
-      res[j][1] = fmaxf(rv.y * rs - p_reg[j][1], 0.f);
-      res[j][2] = fmaxf(rv.z * rs - p_reg[j][2], 0.f);
-      res[j][3] = fmaxf(rv.w * rs - p_reg[j][3], 0.f);
-      z += (res[j][0] + res[j][1]) + (res[j][2] + res[j][3]);
-      *own = make_float4(res[j][0], res[j][1], res[j][2], res[j][3]);
+      rv[j] = *own;
+      float4 res;
+      res.x = fmaxf(rv[j].x * rs - p_reg[j][0], 0.f);
+      res.y = fmaxf(rv[j].y * rs - p_reg[j][1], 0.f);
+      res.z = fmaxf(rv[j].z * rs - p_reg[j][2], 0.f);
+      res.w = fmaxf(rv[j].w * rs - p_reg[j][3], 0.f);
+      z += (res.x + res.y) + (res.z + res.w);
+      *own = res;
     }
     z = wave_sum(z);
     if (lane == 0) s_z[ci & 1][w] = z;
@@ -512,15 +505,18 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     z = combine_sum<NW>(s_z[ci & 1], lane);
     if (z > 0.f) {
       rs = 1.0f / z;
+    } else {
+      // r' == p: nothing left to resample from, and r stays as it was before this child:
+      // put r' back, then undo the move of A's mass
 #pragma unroll
-      for (int j = 0; j < NCH; ++j)
+      for (int j = 0; j < NCH; ++j) *reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]) = rv[j];
+      lds_barrier();
 #pragma unroll
-        for (int e = 0; e < 4; ++e) r_reg[j][e] = res[j][e];
-    } else {  // r' == p: nothing left to resample from; r stays as it was before this child
-#pragma unroll
-      for (int j = 0; j < NCH; ++j)
-        *reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]) =
-            make_float4(r_reg[j][0], r_reg[j][1], r_reg[j][2], r_reg[j][3]);
+      for (int ps = 0; ps < MAXP; ++ps) {
+        if (pm[ps] & 1u) r_lds[pn[ps] & 0xFFFFu] = pv0[ps];
+        if (pm[ps] & 2u) r_lds[pn[ps] >> 16] = pv1[ps];
+      }
+      if (tid == 0) r_lds[t] = rt;
       lds_barrier();
     }
   }
@@ -529,8 +525,8 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   // their owners, then wave 0 finds the cell, the lane and the token.
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    const float cs = (r_reg[j][0] + r_reg[j][1]) + (r_reg[j][2] + r_reg[j][3]);
-    const float tot = wave_sum(cs);
+    const float4 rv = *reinterpret_cast<const float4*>(&r_lds[4 * (tid + NT * j)]);
+    const float tot = wave_sum((rv.x + rv.y) + (rv.z + rv.w));
     if (lane == 0) s_cell[j * NW + w] = tot;
   }
   for (int i = NC + tid; i < 64 * CPL; i += NT) s_cell[i] = 0.f;
@@ -631,7 +627,7 @@ __global__ __launch_bounds__(64) void walk_kernel(VerifyArgs a) {
 template <int NT, int NCH, bool ALIGNED>
 int32_t launch_rows(const VerifyArgs& a, const TreeTab& tt, hipStream_t stream) {
   static size_t attr_lds = 0;   // largest dynamic LDS size this instantiation was enabled for
-  const size_t lds = (size_t)NT * NCH * 4 * sizeof(float) + (size_t)a.nstage * a.kpitch * sizeof(uint16_t);
+  const size_t lds = ((size_t)NT * NCH * 4 + 4) * sizeof(float) + (size_t)a.nstage * NT * sizeof(uint32_t);
   auto kern = verify_rows_kernel<NT, NCH, ALIGNED>;
   if (lds > attr_lds) {
     LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -675,7 +671,6 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
   a.V = V; a.M = tree->M; a.B = B; a.kstride = kstride; a.k = k; a.lambda = lambda;
   a.depth = tree->depth > 0 ? tree->depth : 1;
   a.nstage = std::min<int32_t>(tree->max_children, kMaxStage);
-  a.kpitch = (int32_t)lpp_align_up((size_t)std::min<int32_t>(k, kSlotChunk), 16);
   a.tokens = tokens; a.neigh = neigh; a.u_accept = u_accept; a.u_final = u_final;
   a.decision = out->decision; a.ratio = out->ratio; a.mass = out->mass; a.n_agg = out->n_agg;
   a.q_tok = out->q_tok; a.p_tok = out->p_tok; a.final_all = out->final_tok_all;
@@ -706,7 +701,7 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   auto aligned16 = [&](const float* p) {
-    return p == nullptr || ((reinterpret_cast<uintptr_t>(p + vocab_offset) % 16 == 0) && (ldv % 4 == 0));
+    return p == nullptr || ((reinterpret_cast<uintptr_t>(p + vocab_offset) % 16 == 0) && (ldv % 4 == 0) && (V % 4 == 0));
   };
   const bool al = aligned16(target_logits) && aligned16(drafter_logits);
   int32_t st;
