@@ -6,27 +6,50 @@
 // groups).  A wave owns whole groups and all tree rows of its block's row range:
 //   S^T[32 keys x rows] = K_group * Q^T       (MFMA 16x16x32 bf16, K straight from HBM
 //                                              into the A operand, Q held in registers)
-//   online softmax down the key axis, which is mostly lane-local in this layout
-//   O^T[Dh x rows]    += V_group^T * P^T       (V transposed through a wave-private LDS
-//                                              tile; P never leaves registers)
+//   softmax down the key axis, which is mostly lane-local in this layout; the
+//   reference maximum of a row only moves when a score exceeds it by 2^8, so the
+//   accumulators are rarely rescaled
+//   O^T[Dh x rows]    += V_group^T * P^T       (V rows go to a wave-private LDS tile as
+//                                              they are and come back through the
+//                                              transposing LDS read; P stays in registers;
+//                                              a tile of ones in place of V^T gives the
+//                                              row sums of the rounded P)
+// The loads of a wave's next group are issued before it works on the current one.
 // The ancestor mask is one 64-bit word per (row, 64 tree keys) and only touches
 // tree groups.  Waves of a block merge their (max, sum, O) through LDS; when the
 // key range of one (batch, head) is split over several blocks to fill the chip the
-// partials go through the workspace and a small merge kernel finishes the softmax.
+// partials go through the workspace and the block that finishes last adds them up
+// in split order.
 //
 // fp32 path: a plain wave-per-row kernel for small shapes (no matrix cores).
 #include <math.h>
+#include <stdlib.h>
+
+#include <type_traits>
 
 #include "lpp_internal.h"
 
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kAttnWaves = 4;
-constexpr int kVPitch = 72;          // bytes per row of the transposed V tile (32 keys + pad)
 constexpr float kMasked = -1.0e30f;  // finite stand-in for -inf
+constexpr float kLazy = 8.0f;        // log2 of the largest probability weight before a rescale
+
+// Build with -DLPP_ATTN_TIMESTAMPS to record per-block phase times (100 MHz counter) behind the
+// workspace the caller passes; off in the product build.
+#ifdef LPP_ATTN_TIMESTAMPS
+#define LPP_ATS(i)                                                                                   \
+  do {                                                                                               \
+    if (threadIdx.x == 0) a.ts[(int64_t)blockIdx.x * 16 + (i)] = __builtin_amdgcn_s_memrealtime();  \
+  } while (0)
+#else
+#define LPP_ATS(i) do { } while (0)
+#endif
 
 struct AttnArgs {
   const uint16_t* q;
@@ -38,272 +61,449 @@ struct AttnArgs {
   const uint64_t* anc;
   int32_t B, H, S, M, words;
   int32_t nsplit, msplits, mtiles;   // mtiles = ceil(M / 16)
+  uint32_t rc_perbh, rc_msplits, rc_H, rc_nsplit;   // ceil(2^32 / d): n / d = mulhi(n, rc) while n d < 2^32
   float scale_log2;                  // scale * log2(e)
   float* out;                        // [B,H,M,Dh]
   float* ws_o;                       // [BH][nsplit][mtiles*16][Dh]   unnormalised partial O
-  float* ws_ml;                      // [BH][nsplit][mtiles*16][2]    (max in log2 units, sum)
+  float* ws_ml;                      // [BH][nsplit][mtiles*16][2]    (reference max in log2 units, sum)
+  int32_t* counters;                 // [BH * msplits] zero between calls, or null: separate merge kernel
+#ifdef LPP_ATTN_TIMESTAMPS
+  unsigned long long* ts;            // [blocks][16]
+#endif
 };
 
+// n / d for wave-uniform operands through the host's reciprocal: scalar multiplies, no division
+__device__ __forceinline__ uint32_t div_rc(uint32_t n, uint32_t d, uint32_t rc) {
+  const uint32_t q = (uint32_t)(((uint64_t)n * rc) >> 32);   // (rc = 0 for d = 1)
+  return rc == 0 ? n : q;
+}
 __device__ __forceinline__ uint4 ld16(const uint16_t* p) {
   return *reinterpret_cast<const uint4*>(p);
 }
-__device__ __forceinline__ uint32_t bf16_rne(float x) {  // finite inputs only
-  uint32_t u = __float_as_uint(x);
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
 __device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
   __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round to nearest even (hardware convert)
+  const bf16x2 v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
 }
 
-template <int DH, int NT>
-__global__ __launch_bounds__(kAttnWaves * 64) void tree_attn_bf16_kernel(AttnArgs a) {
+// One key group in flight: K as the A operand of S^T = K Q^T, V as loaded (row-major chunks).
+template <int DH>
+struct Stage {
+  bf16x8 ka[2][DH / 32];
+  uint4 vr[DH / 16];     // chunk c = lane + 64 p of the group's 32 x (DH/8) 16-byte chunks
+};
+
+// NT = row tiles (of 16 tree rows) per wave, RW = waves along the rows, KW = waves along the keys:
+// a block covers NT * RW * 16 tree rows; wave (kw, rw) takes key groups gbeg + kw, + KW, ... for
+// rows [rw NT 16, (rw + 1) NT 16).  The RW waves that share a key group load it independently; the
+// second read is served by the compute unit's own cache.
+template <int DH, int NT, int RW, int KW>
+__global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a) {
+  static_assert(RW == 1, "a block is one row range; its waves split the keys");
+  constexpr int W = RW * KW;
   constexpr int KS = DH / 32;        // contraction steps of Q K^T
   constexpr int DT = DH / 16;        // Dh tiles of the output
   constexpr int CPR = DH / 8;        // 16-byte chunks per K/V row
-  constexpr int QPP = 64 / CPR;      // key quads per V load pass
-  constexpr int VP = 8 / QPP;        // V load passes per 32-key group
-  constexpr int ROWS = NT * 16;
+  constexpr int VCH = DH / 16;       // V chunks per lane and group
+  constexpr int VPITCH = DH * 2 + 32;   // bytes per key of the LDS V tile: 32 mod 256, so that the
+                                        // 16 keys x 32 bytes of a transposing read hit all banks once
+  constexpr int VTILE = 32 * VPITCH;
+  constexpr int WROWS = NT * 16;     // rows of a wave
+  constexpr int ROWS = RW * WROWS;   // rows of the block
   constexpr int OPITCH = DH + 4;     // floats per row of the merge buffer
-  extern __shared__ unsigned char smem[];
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_ticket;
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l16 = lane & 15, g4 = lane >> 4;
+  const int kw = wave % KW, rw = wave / KW;
+  LPP_ATS(0);
 
   // block -> (batch*head, key split, row split); all blocks of one head share an XCD
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int per_bh = a.nsplit * a.msplits;
+  const uint32_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const uint32_t per_bh = (uint32_t)(a.nsplit * a.msplits);
+  const uint32_t hq = div_rc(slot, per_bh, a.rc_perbh), hr = slot - hq * per_bh;
   const int BH = a.B * a.H;
-  const int bh = (slot / per_bh) * 8 + xcd;
-  if (bh >= BH) return;
-  const int split = (slot % per_bh) / a.msplits, ms = (slot % per_bh) % a.msplits;
-  const int b = bh / a.H;
+  // (no early exit for the padding blocks of the last XCD round: a branch here would keep every
+  // later argument load behind it; they redo the last head's work and write nothing)
+  const bool live = (int)(hq * 8 + xcd) < BH;
+  const int bh = min((int)(hq * 8 + xcd), BH - 1);
+  const int split = (int)div_rc(hr, (uint32_t)a.msplits, a.rc_msplits), ms = (int)hr - split * a.msplits;
+  const int b = (int)div_rc((uint32_t)bh, (uint32_t)a.H, a.rc_H);
   const int M = a.M, S = a.S;
-  const int m0 = ms * ROWS;
-  int seq = S;
-  if (a.seq_len) seq = min(max(a.seq_len[b], 0), S);
+  const int m0 = ms * ROWS + rw * WROWS;       // first row of this wave
+  // (branch-free: with no seq_len array the load goes to a valid dummy address)
+  const int32_t* slp = a.seq_len ? a.seq_len + b : reinterpret_cast<const int32_t*>(a.q);
+  const int slv = *slp;
+  const int seq = a.seq_len ? min(max(slv, 0), S) : S;
   const int GC = (seq + 31) >> 5, GT = (M + 31) >> 5, G = GC + GT;
-  const int gbeg = (int)(((long long)split * G) / a.nsplit);
-  const int gend = (int)(((long long)(split + 1) * G) / a.nsplit);
+  const int gbeg = (int)div_rc((uint32_t)(split * G), (uint32_t)a.nsplit, a.rc_nsplit);
+  const int gend = (int)div_rc((uint32_t)((split + 1) * G), (uint32_t)a.nsplit, a.rc_nsplit);
+  const uint16_t* kc = a.kc + (int64_t)bh * S * DH;
+  const uint16_t* vc = a.vc + (int64_t)bh * S * DH;
+  const uint16_t* kt = a.kt + (int64_t)bh * M * DH;
+  const uint16_t* vt = a.vt + (int64_t)bh * M * DH;
+
+  // Key groups [0, GF) lie wholly inside the cache: no mask, no bounds.  The others (the ragged
+  // end of the cache and the tree keys) go through the general path after them.
+  const int GF = seq >> 5;
+  const uint32_t koff = (uint32_t)(l16 * DH + g4 * 8);                      // my K chunk inside a group
+  const uint32_t voff = (uint32_t)((lane / CPR) * DH + (lane % CPR) * 8);   // my V chunks: + p * (64 / CPR) rows
+  auto load_full = [&](Stage<DH>& st, int g) {
+    const uint16_t* Kp = kc + (int64_t)g * (32 * DH);
+    const uint16_t* Vp = vc + (int64_t)g * (32 * DH);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        st.ka[t][ks] = __builtin_bit_cast(bf16x8, ld16(Kp + (koff + (uint32_t)(t * 16 * DH + ks * 32))));
+#pragma unroll
+    for (int p = 0; p < VCH; ++p) st.vr[p] = ld16(Vp + (voff + (uint32_t)(p * (64 / CPR) * DH)));
+  };
+  // general path: every load is unconditional and in bounds (row index clamped); absent keys are
+  // masked out of the scores, and their V rows are zeroed on the way into LDS
+  auto load_any = [&](Stage<DH>& st, int g) {
+    const bool is_tree = g >= GC;
+    const int kbase = is_tree ? (g - GC) * 32 : g * 32;
+    const int last = (is_tree ? M : seq) - 1;
+    const uint16_t* Kp = is_tree ? kt : kc;
+    const uint16_t* Vp = is_tree ? vt : vc;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int row = min(kbase + t * 16 + l16, last);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        st.ka[t][ks] = __builtin_bit_cast(bf16x8, ld16(Kp + (uint32_t)(row * DH + ks * 32 + g4 * 8)));
+    }
+#pragma unroll
+    for (int p = 0; p < VCH; ++p) {
+      const int c = lane + 64 * p;
+      const int row = min(kbase + c / CPR, last);
+      st.vr[p] = ld16(Vp + (uint32_t)(row * DH + (c % CPR) * 8));
+    }
+  };
 
   // Q as the B operand: column = tree row, 8 consecutive Dh per lane and step
   bf16x8 qb[NT][KS];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    const int m = m0 + nt * 16 + l16;
+    const int m = min(m0 + nt * 16 + l16, M - 1);
 #pragma unroll
-    for (int st = 0; st < KS; ++st) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (m < M) v = ld16(a.q + ((int64_t)bh * M + m) * DH + st * 32 + g4 * 8);
-      qb[nt][st] = __builtin_bit_cast(bf16x8, v);
-    }
+    for (int ks = 0; ks < KS; ++ks)
+      qb[nt][ks] = __builtin_bit_cast(bf16x8, ld16(a.q + (int64_t)bh * M * DH + (uint32_t)(m * DH + ks * 32 + g4 * 8)));
   }
 
-  f32x4 oacc[DT][NT];
-  float m_run[NT], l_part[NT];
+  f32x4 oacc[DT][NT], lacc[NT];
+  float m_ref[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    m_run[nt] = kMasked;
-    l_part[nt] = 0.f;
+    m_ref[nt] = kMasked;
+    lacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) oacc[dt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
+  const uint32_t one2 = 0x3F803F80u;   // two bf16 ones
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(one2, one2, one2, one2));
 
-  unsigned char* vtile = smem + wave * (DH * kVPitch);
-  const int vq = lane / CPR, vc8 = lane % CPR;   // V load role: key quad, 8-wide Dh chunk
+  unsigned char* vtile = smem + wave * (2 * VTILE);
+  int buf = 0;
+  const uint32_t vst = (uint32_t)((lane / CPR) * VPITCH + (lane % CPR) * 16);           // where my V chunks go
+  const uint32_t vld = (uint32_t)((4 * g4 + (l16 >> 2)) * VPITCH + 8 * (l16 & 3));     // what I point the transposing read at
 
-  for (int g = gbeg + wave; g < gend; g += kAttnWaves) {
+  // Which of the 32 keys of group g row m0 + nt 16 + l16 may see: the ancestor mask for tree
+  // keys, the valid length for the ragged end of the cache.  The mask words are fetched here and
+  // only looked at inside compute_group, so that the fetch does not hold up what follows.
+  auto visibility = [&](uint64_t (&vis)[NT], int g) {
+    const bool is_tree = g >= GC;
+    const int kbase = is_tree ? (g - GC) * 32 : 0;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int m = min(m0 + nt * 16 + l16, M - 1);   // (rows past M are never written out)
+      vis[nt] = a.anc[m * a.words + (kbase >> 6)];     // (a valid word also for cache groups: unused there)
+    }
+  };
+
+  // One key group.  FULL (compile time): all 32 keys present and visible to every row.
+  auto compute_group = [&](const Stage<DH>& st, int g, const uint64_t (&vis)[NT], auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
     const bool is_tree = g >= GC;
     const int kbase = is_tree ? (g - GC) * 32 : g * 32;
     const int limit = is_tree ? M : seq;                       // keys [kbase, limit) exist
-    const uint16_t* Kp = is_tree ? a.kt + (int64_t)bh * M * DH : a.kc + (int64_t)bh * S * DH;
-    const uint16_t* Vp = is_tree ? a.vt + (int64_t)bh * M * DH : a.vc + (int64_t)bh * S * DH;
-
-    bf16x8 ka[2][KS];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      const int row = min(kbase + kt * 16 + l16, limit - 1);
-#pragma unroll
-      for (int st = 0; st < KS; ++st)
-        ka[kt][st] = __builtin_bit_cast(bf16x8, ld16(Kp + (int64_t)row * DH + st * 32 + g4 * 8));
-    }
-    uint4 vr[VP][4];
-#pragma unroll
-    for (int ps = 0; ps < VP; ++ps)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = kbase + (ps * QPP + vq) * 4 + i;
-        vr[ps][i] = make_uint4(0, 0, 0, 0);                    // absent keys contribute exact zeros
-        if (row < limit) vr[ps][i] = ld16(Vp + (int64_t)row * DH + vc8 * 8);
-      }
 
     // S^T = K Q^T
     f32x4 sacc[2][NT];
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        sacc[kt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        sacc[t][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int st = 0; st < KS; ++st)
-          sacc[kt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt][st], qb[nt][st], sacc[kt][nt], 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks)
+          sacc[t][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.ka[t][ks], qb[nt][ks], sacc[t][nt], 0, 0, 0);
       }
 
-    // online softmax over this group's 32 keys; lane holds keys kt*16 + 4*g4 + r of column l16
+    // V rows into this wave's LDS tile, as they are
+    unsigned char* tile = vtile + buf * VTILE;
+#pragma unroll
+    for (int p = 0; p < VCH; ++p) {
+      uint4 v = st.vr[p];
+      if (!FULL && kbase + (lane + 64 * p) / CPR >= limit) v = make_uint4(0, 0, 0, 0);   // absent keys: exact zeros
+      *reinterpret_cast<uint4*>(tile + vst + p * (64 / CPR) * VPITCH) = v;
+    }
+
+    // softmax weights of the group; lane holds keys t*16 + 4*g4 + r of column l16
+    uint32_t bits[NT];
+    float mxl[NT];
+    bool need = false;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      bits[nt] = 0xFFFFFFFFu;
+      if (!FULL) {
+        const int left = seq - kbase;
+        const uint32_t cache_bits = left >= 32 ? 0xFFFFFFFFu : ((1u << left) - 1u);
+        bits[nt] = is_tree ? (uint32_t)(vis[nt] >> (kbase & 63)) : cache_bits;
+        bits[nt] >>= 4 * g4;        // bit 16 t + r is now my key (t, r)
+      }
+      float v = kMasked;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float sc = sacc[t][nt][r];
+          if (!FULL && !((bits[nt] >> (16 * t + r)) & 1u)) sc = kMasked;
+          v = fmaxf(v, sc);
+        }
+      mxl[nt] = v > 0.5f * kMasked ? v * a.scale_log2 : kMasked;   // (scale > 0: the maximum commutes with it)
+      need = need || (mxl[nt] > m_ref[nt] + kLazy);
+    }
+    if (__ballot(need)) {   // some row's reference moves: rare after a wave's first group
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        float v = mxl[nt];
+        v = fmaxf(v, __shfl_xor(v, 16));
+        v = fmaxf(v, __shfl_xor(v, 32));
+        const bool up = v > m_ref[nt] + kLazy;                 // decided per row: no row depends on another's scores
+        const float nm = up ? v : m_ref[nt];
+        const float alpha = __builtin_amdgcn_exp2f(m_ref[nt] - nm);
+        m_ref[nt] = nm;
+        lacc[nt] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) oacc[dt][nt] *= alpha;
+      }
+    }
     bf16x8 pb[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      const int m = m0 + nt * 16 + l16;
-      uint32_t bits;
-      if (is_tree) {
-        bits = 0;
-        if (m < M) bits = (uint32_t)(a.anc[(int64_t)m * a.words + (kbase >> 6)] >> (kbase & 63));
-      } else {
-        const int left = seq - kbase;
-        bits = left >= 32 ? 0xFFFFFFFFu : ((1u << left) - 1u);
-      }
-      float sv[2][4];
-      float mx = m_run[nt];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const bool on = (bits >> (kt * 16 + 4 * g4 + r)) & 1u;
-          sv[kt][r] = on ? sacc[kt][nt][r] * a.scale_log2 : kMasked;
-          mx = fmaxf(mx, sv[kt][r]);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - mx);
-      m_run[nt] = mx;
       uint32_t pk[4];
-      float psum = 0.f;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 4; r += 2) {
-          const float p0 = sv[kt][r] > 0.5f * kMasked ? __builtin_amdgcn_exp2f(sv[kt][r] - mx) : 0.f;
-          const float p1 = sv[kt][r + 1] > 0.5f * kMasked ? __builtin_amdgcn_exp2f(sv[kt][r + 1] - mx) : 0.f;
-          const uint32_t h0 = bf16_rne(p0), h1 = bf16_rne(p1);
-          psum += __uint_as_float(h0 << 16) + __uint_as_float(h1 << 16);
-          pk[kt * 2 + r / 2] = h0 | (h1 << 16);
+          float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[t][nt][r], a.scale_log2, -m_ref[nt]));
+          float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[t][nt][r + 1], a.scale_log2, -m_ref[nt]));
+          if (!FULL) {
+            if (!((bits[nt] >> (16 * t + r)) & 1u)) p0 = 0.f;
+            if (!((bits[nt] >> (16 * t + r + 1)) & 1u)) p1 = 0.f;
+          }
+          pk[t * 2 + r / 2] = pack_bf16(p0, p1);
         }
-      l_part[nt] = l_part[nt] * alpha + psum;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) oacc[dt][nt] *= alpha;
       pb[nt] = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+      lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[nt], lacc[nt], 0, 0, 0);
     }
 
-    // V^T through the wave-private LDS tile: [Dh][32 keys] bf16
-    wave_lds_sync();   // the previous group's reads are done
-#pragma unroll
-    for (int ps = 0; ps < VP; ++ps) {
-      const int quad = ps * QPP + vq;
-      const uint32_t w0[4] = {vr[ps][0].x, vr[ps][0].y, vr[ps][0].z, vr[ps][0].w};
-      const uint32_t w1[4] = {vr[ps][1].x, vr[ps][1].y, vr[ps][1].z, vr[ps][1].w};
-      const uint32_t w2[4] = {vr[ps][2].x, vr[ps][2].y, vr[ps][2].z, vr[ps][2].w};
-      const uint32_t w3[4] = {vr[ps][3].x, vr[ps][3].y, vr[ps][3].z, vr[ps][3].w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        uint2 lo, hi;   // Dh element 2j and 2j+1 of the chunk, keys quad*4 .. +3
-        lo.x = __builtin_amdgcn_perm(w1[j], w0[j], 0x05040100u);
-        lo.y = __builtin_amdgcn_perm(w3[j], w2[j], 0x05040100u);
-        hi.x = __builtin_amdgcn_perm(w1[j], w0[j], 0x07060302u);
-        hi.y = __builtin_amdgcn_perm(w3[j], w2[j], 0x07060302u);
-        *reinterpret_cast<uint2*>(vtile + (vc8 * 8 + 2 * j) * kVPitch + quad * 8) = lo;
-        *reinterpret_cast<uint2*>(vtile + (vc8 * 8 + 2 * j + 1) * kVPitch + quad * 8) = hi;
-      }
-    }
+    // O^T += V^T P^T.  Contraction slot (g4, j) is key (j < 4 ? 0 : 16) + 4 g4 + j % 4 on both sides.
+    // The transposing read hands lane (l16, g4) the four values V[key 4 g4 + j][dt 16 + l16]: within a
+    // group of 16 lanes, lane s points at 4 consecutive Dh of key 4 g4 + s / 4 at Dh offset 4 (s % 4).
     wave_lds_sync();
-    // O^T += V^T P^T ; contraction slot (g4, j) is key (j<4 ? 0 : 16) + 4*g4 + j%4 on both sides
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      const unsigned char* rowp = vtile + (dt * 16 + l16) * kVPitch + g4 * 8;
-      const uint2 a0 = *reinterpret_cast<const uint2*>(rowp);
-      const uint2 a1 = *reinterpret_cast<const uint2*>(rowp + 32);
-      const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(a0.x, a0.y, a1.x, a1.y));
+      const unsigned char* src = tile + vld + dt * 32;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (s16x4 __attribute__((address_space(3)))*)(const __attribute__((address_space(3))) unsigned char*)src);
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (s16x4 __attribute__((address_space(3)))*)(const __attribute__((address_space(3))) unsigned char*)(src + 16 * VPITCH));
+      const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+      const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(l2.x, l2.y, h2.x, h2.y));
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
         oacc[dt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[nt], oacc[dt][nt], 0, 0, 0);
     }
+    buf ^= 1;   // the next group writes the other tile while these reads may still be in flight
+  };
+  const std::integral_constant<bool, true> kFull;
+  const std::integral_constant<bool, false> kAny;
+
+  // ---- this wave's groups.  Its first general group is fetched before anything else and worked
+  // on while the loads of the full groups are in flight; those go through a ring of D stages: the
+  // loads of the next D - 1 groups are in flight while one is worked on, and a stage is refilled
+  // as soon as it has been consumed.
+  {
+    const int h1 = min(gend, GF);                     // full groups: [gbeg, h1)
+    const int c0 = max(gbeg, GF);                     // general groups: [c0, gend)
+    const uint64_t novis[NT] = {};
+    Stage<DH> cst;
+    uint64_t vis[NT];
+    int gx = c0 + kw;                                 // next general group of this wave
+    if (GF >= 1) {
+      constexpr int D = DH == 64 ? 4 : 2;
+      Stage<DH> st[D];
+      const bool pre = gx < gend;
+      if (pre) { visibility(vis, gx); load_any(cst, gx); }
+      // Ring loads are issued unconditionally (a group index past the end is clamped: a re-read
+      // that is never used), so that the number of loads in flight is the same on every path and
+      // each wait lets the younger loads stay in flight.
+      int g = gbeg + kw;
+      const int hl = max(h1 - 1, 0);
+      LPP_ATS(7);
+#pragma unroll
+      for (int d = 0; d < D; ++d) load_full(st[d], min(g + d * KW, hl));
+      if (pre) { compute_group(cst, gx, vis, kAny); gx += KW; }
+      while (g + (D - 1) * KW < h1) {             // whole rounds of the ring
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+          compute_group(st[d], g, novis, kFull);
+          load_full(st[d], min(g + D * KW, hl));
+          g += KW;
+        }
+      }
+#pragma unroll
+      for (int d = 0; d < D - 1; ++d) {           // what is left: fewer than D groups, already loaded
+        if (g < h1) compute_group(st[d], g, novis, kFull);
+        g += KW;
+      }
+    }
+    for (; gx < gend; gx += KW) {                 // further general groups: rare, not pipelined
+      visibility(vis, gx);
+      load_any(cst, gx);
+      compute_group(cst, gx, vis, kAny);
+    }
   }
 
-  // ---- merge the waves of this block (fixed order => run-to-run identical)
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    l_part[nt] += __shfl_xor(l_part[nt], 16);
-    l_part[nt] += __shfl_xor(l_part[nt], 32);
-  }
-  __syncthreads();   // every wave is done with its V tile: the buffer is reused below
-  float* s_o = reinterpret_cast<float*>(smem);                  // [ROWS][OPITCH]
-  float* s_m = s_o + ROWS * OPITCH;                             // [waves][ROWS]
-  float* s_l = s_m + kAttnWaves * ROWS;                         // [waves][ROWS]
+  // ---- merge the waves of the block (fixed order => run-to-run identical): every wave brings
+  // its O to the block's reference maximum and parks it in LDS; the sum over the waves is taken
+  // on the way out
+  LPP_ATS(1);
+#ifdef LPP_ATTN_TIMESTAMPS
+  if (lane == 0) a.ts[(int64_t)blockIdx.x * 16 + 8 + wave] = __builtin_amdgcn_s_memrealtime();
+#endif
+  __syncthreads();   // every wave is done with its V tiles: the buffer is reused below
+  LPP_ATS(2);
+  float* s_o = reinterpret_cast<float*>(smem);                  // [W][ROWS][OPITCH]
+  float* s_m = s_o + W * ROWS * OPITCH;                         // [W][ROWS], then the block's: [ROWS]
+  float* s_l = s_m + (W + 1) * ROWS;                            // [W][ROWS], then the block's: [ROWS]
+  const int r0 = rw * WROWS;                                    // my first row inside the block
   if (g4 == 0) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      s_m[wave * ROWS + nt * 16 + l16] = m_run[nt];
-      s_l[wave * ROWS + nt * 16 + l16] = l_part[nt];
+      s_m[wave * ROWS + r0 + nt * 16 + l16] = m_ref[nt];
+      s_l[wave * ROWS + r0 + nt * 16 + l16] = lacc[nt][0];
     }
   }
   __syncthreads();
-  float mtot[NT], ltot[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    const int col = nt * 16 + l16;
-    float mm = s_m[col];
+    const int col = r0 + nt * 16 + l16;
+    float mm = kMasked;
 #pragma unroll
-    for (int w = 1; w < kAttnWaves; ++w) mm = fmaxf(mm, s_m[w * ROWS + col]);
+    for (int w = 0; w < KW; ++w) mm = fmaxf(mm, s_m[(rw * KW + w) * ROWS + col]);
     float ll = 0.f;
 #pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w)
-      ll += __builtin_amdgcn_exp2f(s_m[w * ROWS + col] - mm) * s_l[w * ROWS + col];
-    mtot[nt] = mm;
-    ltot[nt] = ll;
-    const float f = __builtin_amdgcn_exp2f(m_run[nt] - mm);
+    for (int w = 0; w < KW; ++w)
+      ll += __builtin_amdgcn_exp2f(s_m[(rw * KW + w) * ROWS + col] - mm) * s_l[(rw * KW + w) * ROWS + col];
+    const float f = __builtin_amdgcn_exp2f(m_ref[nt] - mm);
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) oacc[dt][nt] *= f;
-  }
-  for (int w = 0; w < kAttnWaves; ++w) {
-    if (wave == w) {
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          float4* dst = reinterpret_cast<float4*>(&s_o[(nt * 16 + l16) * OPITCH + dt * 16 + 4 * g4]);
-          float4 v = make_float4(oacc[dt][nt][0], oacc[dt][nt][1], oacc[dt][nt][2], oacc[dt][nt][3]);
-          if (w > 0) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
-          *dst = v;
-        }
+    for (int dt = 0; dt < DT; ++dt) {
+      float4* dst = reinterpret_cast<float4*>(&s_o[(kw * ROWS + col) * OPITCH + dt * 16 + 4 * g4]);
+      *dst = make_float4(oacc[dt][nt][0] * f, oacc[dt][nt][1] * f, oacc[dt][nt][2] * f, oacc[dt][nt][3] * f);
     }
-    __syncthreads();
-  }
-  if (wave == 0 && g4 == 0) {   // totals for the write-out below
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      s_m[nt * 16 + l16] = mtot[nt];
-      s_l[nt * 16 + l16] = ltot[nt];
-    }
+    if (kw == 0 && g4 == 0) { s_m[W * ROWS + col] = mm; s_l[W * ROWS + col] = ll; }
   }
   __syncthreads();
+  LPP_ATS(3);
 
   // ---- write: final rows if this block saw every key, else an unnormalised partial
   constexpr int C4 = DH / 4;
-  for (int idx = threadIdx.x; idx < ROWS * C4; idx += kAttnWaves * 64) {
+  const int rows_pad = a.mtiles * 16;
+  const int mb = ms * ROWS;                                     // first row of the block
+  for (int idx = threadIdx.x; idx < ROWS * C4; idx += W * 64) {
     const int r = idx / C4, c4 = idx % C4;
-    const int m = m0 + r;
-    if (m >= M) continue;
+    const int m = mb + r;
+    if (m >= M || !live) continue;
     float4 v = *reinterpret_cast<const float4*>(&s_o[r * OPITCH + c4 * 4]);
+#pragma unroll
+    for (int w = 1; w < KW; ++w) {
+      const float4 o = *reinterpret_cast<const float4*>(&s_o[(w * ROWS + r) * OPITCH + c4 * 4]);
+      v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+    }
+    const float bm = s_m[W * ROWS + r], bl = s_l[W * ROWS + r];
     if (a.nsplit == 1) {
-      const float inv = 1.0f / s_l[r];
+      const float inv = 1.0f / bl;
       v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
       *reinterpret_cast<float4*>(a.out + ((int64_t)bh * M + m) * DH + c4 * 4) = v;
     } else {
-      const int64_t prow = ((int64_t)bh * a.nsplit + split) * (a.mtiles * 16) + m;
-      *reinterpret_cast<float4*>(a.ws_o + prow * DH + c4 * 4) = v;
-      if (c4 == 0) { a.ws_ml[prow * 2] = s_m[r]; a.ws_ml[prow * 2 + 1] = s_l[r]; }
+      const int64_t prow = ((int64_t)bh * a.nsplit + split) * rows_pad + m;
+      float* dst = a.ws_o + prow * DH + c4 * 4;
+      if (a.counters) {   // read by another block of this launch: stores that are visible device-wide when they complete
+        __hip_atomic_store(dst + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(dst + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(dst + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(dst + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (c4 == 0) {
+          __hip_atomic_store(&a.ws_ml[prow * 2], bm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(&a.ws_ml[prow * 2 + 1], bl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      } else {
+        *reinterpret_cast<float4*>(dst) = v;
+        if (c4 == 0) { a.ws_ml[prow * 2] = bm; a.ws_ml[prow * 2 + 1] = bl; }
+      }
     }
   }
+  LPP_ATS(4);
+  if (a.nsplit == 1 || !a.counters || !live) return;
+
+  // ---- the block of this (head, row range) that finishes last adds the splits up, in split order
+  // The barrier waits until this block's partial has been written (device-scope stores complete
+  // when they are visible to every compute unit); the ticket and the reads below are device-scope
+  // atomics as well, so no cache write-back or invalidate is needed.
+  __syncthreads();
+  if (threadIdx.x == 0)
+    s_ticket = __hip_atomic_fetch_add(&a.counters[bh * a.msplits + ms], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  LPP_ATS(5);
+  if (s_ticket != a.nsplit - 1) return;
+  for (int idx = threadIdx.x; idx < ROWS * C4; idx += W * 64) {
+    const int r = idx / C4, c4 = idx % C4;
+    const int m = mb + r;
+    if (m >= M) continue;
+    float mm = kMasked;
+    for (int sp = 0; sp < a.nsplit; ++sp) {
+      const int64_t prow = ((int64_t)bh * a.nsplit + sp) * rows_pad + m;
+      mm = fmaxf(mm, __hip_atomic_load(&a.ws_ml[prow * 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    }
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float ll = 0.f;
+    for (int sp = 0; sp < a.nsplit; ++sp) {
+      const int64_t prow = ((int64_t)bh * a.nsplit + sp) * rows_pad + m;
+      const float f = __builtin_amdgcn_exp2f(
+          __hip_atomic_load(&a.ws_ml[prow * 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - mm);
+      ll += f * __hip_atomic_load(&a.ws_ml[prow * 2 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const float* src = a.ws_o + prow * DH + c4 * 4;
+      acc.x += f * __hip_atomic_load(src + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      acc.y += f * __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      acc.z += f * __hip_atomic_load(src + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      acc.w += f * __hip_atomic_load(src + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const float inv = 1.0f / ll;
+    *reinterpret_cast<float4*>(a.out + ((int64_t)bh * M + m) * DH + c4 * 4) =
+        make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+  }
+  LPP_ATS(6);
+  if (threadIdx.x == 0)   // ready for the next call
+    __hip_atomic_store(&a.counters[bh * a.msplits + ms], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Finish the softmax across the key splits of one (batch, head): one lane per 4 output floats.
@@ -350,8 +550,10 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = blockIdx.x, bh = blockIdx.y, b = bh / a.H;
   const int Dh = a.Dh, M = a.M, S = a.S;
-  int seq = S;
-  if (a.seq_len) seq = min(max(a.seq_len[b], 0), S);
+  // (branch-free: with no seq_len array the load goes to a valid dummy address)
+  const int32_t* slp = a.seq_len ? a.seq_len + b : reinterpret_cast<const int32_t*>(a.q);
+  const int slv = *slp;
+  const int seq = a.seq_len ? min(max(slv, 0), S) : S;
   const float* qrow = a.q + ((int64_t)bh * M + m) * Dh;
   const float q0 = lane < Dh ? qrow[lane] : 0.f;
   const float q1 = lane + 64 < Dh ? qrow[lane + 64] : 0.f;
@@ -397,43 +599,50 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
 }
 
 struct AttnPlan {
-  int nt, msplits, nsplit, mtiles;
+  int nt, kw, msplits, nsplit, mtiles;
   size_t lds;
 };
 
+// A block is one range of NT * 16 tree rows of one (batch, head) and one range of key groups;
+// its KW waves take the key groups in turn.  The blocks of a head that differ in the row range
+// read the same keys at about the same time and sit on the same XCD, so that the second read is
+// served by its L2.  Key splits (which cost a pass through the workspace) are only added while
+// the grid would leave compute units idle.
 AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh) {
   AttnPlan p;
   p.mtiles = (tree->M + 15) / 16;
-  const int max_nt = Dh == 64 ? 5 : 4;
-  p.msplits = (p.mtiles + max_nt - 1) / max_nt;
-  p.nt = (p.mtiles + p.msplits - 1) / p.msplits;
+  p.nt = p.mtiles == 1 ? 1 : 2;
+  p.msplits = (p.mtiles + p.nt - 1) / p.nt;
+  p.kw = 8;
   const int G = (S + 31) / 32 + (tree->M + 31) / 32;
   const int blocks_bh = B * H * p.msplits;
-  int ns = (3 * 256 + blocks_bh - 1) / blocks_bh;          // aim at ~3 blocks per CU
-  const int max_ns = (G + kAttnWaves - 1) / kAttnWaves;    // at least one group per wave
+  int ns = 256 / blocks_bh;                       // one block of 8 waves per compute unit
+  const int max_ns = G / (2 * p.kw);              // at least two key groups per wave
   if (ns > max_ns) ns = max_ns;
   if (ns < 1) ns = 1;
+  if (const char* e = getenv("LPP_ATTN_NSPLIT")) { const int v = atoi(e); if (v >= 1 && v <= G) ns = v; }
   p.nsplit = ns;
-  const size_t vt = (size_t)kAttnWaves * Dh * kVPitch;
-  const size_t mg = ((size_t)p.nt * 16 * (Dh + 4) + 2 * kAttnWaves * p.nt * 16) * sizeof(float);
+  const int rows = p.nt * 16;
+  const size_t vt = (size_t)p.kw * 2 * 32 * (Dh * 2 + 32);
+  const size_t mg = ((size_t)p.kw * rows * (Dh + 4) + 2 * (p.kw + 1) * rows) * sizeof(float);
   p.lds = vt > mg ? vt : mg;
   return p;
 }
 
-template <int DH, int NT>
+template <int DH, int NT, int RW, int KW>
 int32_t launch_bf16(const AttnArgs& a, const AttnPlan& p, hipStream_t s) {
-  static bool attr_set = false;
-  auto kern = tree_attn_bf16_kernel<DH, NT>;
-  if (!attr_set && p.lds > 48 * 1024) {
+  static size_t attr_lds = 48 * 1024;   // largest dynamic LDS size this instantiation was enabled for
+  auto kern = tree_attn_bf16_kernel<DH, NT, RW, KW>;
+  if (p.lds > attr_lds) {
     LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds));
-    attr_set = true;
+    attr_lds = p.lds;
   }
   const int BH = a.B * a.H;
   const unsigned blocks = 8u * ((BH + 7) / 8) * p.nsplit * p.msplits;
-  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kAttnWaves * 64), p.lds, s, a);
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(RW * KW * 64), p.lds, s, a);
   LPP_HIP_TRY(hipGetLastError());
-  if (p.nsplit > 1) {
+  if (p.nsplit > 1 && !a.counters) {
     const int64_t total = (int64_t)BH * a.M * (DH / 4);
     hipLaunchKernelGGL(tree_attn_merge_kernel<DH>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);
     LPP_HIP_TRY(hipGetLastError());
@@ -461,7 +670,8 @@ extern "C" int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype, const
   if (scale != scale) return LPP_EINVAL;
   if (Dh != 64 && Dh != 128) return LPP_EUNSUPPORTED;
   if (dtype != LPP_F32 && dtype != LPP_BF16) return LPP_EUNSUPPORTED;
-  if ((int64_t)B * H > (1 << 24)) return LPP_EUNSUPPORTED;
+  if ((int64_t)B * H > (1 << 24) || (int64_t)B * H * H >= (1ll << 32)) return LPP_EUNSUPPORTED;
+  if ((int64_t)S * Dh >= (1ll << 31) || (int64_t)tree->M * Dh >= (1ll << 31)) return LPP_EUNSUPPORTED;   // 32-bit offsets inside one head
   const size_t need = lpp_tree_attention_workspace(tree, B, H, S, Dh);
   if (!ws || ws_bytes < need) return LPP_ENOWORKSPACE;
   if (!tree->d_anc) return LPP_EHIP;
@@ -484,28 +694,25 @@ extern "C" int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype, const
   a.kt = (const uint16_t*)k_tree; a.vt = (const uint16_t*)v_tree; a.seq_len = seq_len; a.anc = tree->d_anc;
   a.B = B; a.H = H; a.S = S; a.M = tree->M; a.words = tree->words;
   a.nsplit = p.nsplit; a.msplits = p.msplits; a.mtiles = p.mtiles;
+  auto rc = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((0x100000000ull + d - 1) / d); };
+  a.rc_perbh = rc((uint32_t)(p.nsplit * p.msplits)); a.rc_msplits = rc((uint32_t)p.msplits);
+  a.rc_H = rc((uint32_t)H); a.rc_nsplit = rc((uint32_t)p.nsplit);
   a.scale_log2 = scale * 1.44269504088896340736f;
   a.out = out;
+  a.counters = (int64_t)B * H * p.msplits <= LPP_COUNTER_SLOTS ? tree->d_counters + LPP_COUNTER_SLOTS : nullptr;
   const size_t rows = (size_t)B * H * p.nsplit * p.mtiles * 16;
+#ifdef LPP_ATTN_TIMESTAMPS
+  a.ts = reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(ws) + need);
+#endif
   a.ws_o = reinterpret_cast<float*>(ws);
   a.ws_ml = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(ws) + lpp_align_up(rows * Dh * sizeof(float), 256));
 
-#define LPP_ATTN(DHV, NTV) return launch_bf16<DHV, NTV>(a, p, s)
-  if (Dh == 64) {
-    switch (p.nt) {
-      case 1: LPP_ATTN(64, 1);
-      case 2: LPP_ATTN(64, 2);
-      case 3: LPP_ATTN(64, 3);
-      case 4: LPP_ATTN(64, 4);
-      default: LPP_ATTN(64, 5);
-    }
-  } else {
-    switch (p.nt) {
-      case 1: LPP_ATTN(128, 1);
-      case 2: LPP_ATTN(128, 2);
-      case 3: LPP_ATTN(128, 3);
-      default: LPP_ATTN(128, 4);
-    }
-  }
+#define LPP_ATTN(DHV)                                                        \
+  do {                                                                       \
+    if (p.nt == 1) return launch_bf16<DHV, 1, 1, 8>(a, p, s);                \
+    return launch_bf16<DHV, 2, 1, 8>(a, p, s);                               \
+  } while (0)
+  if (Dh == 64) LPP_ATTN(64);
+  LPP_ATTN(128);
 #undef LPP_ATTN
 }
