@@ -21,6 +21,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+# HBM bytes per launch at config 3 from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (profiles/), scaled
+# by the same counters' reading for a copy of known size; None until measured for a kernel.
+TRAFFIC = {"tree_attention": 29.30e6, "relaxed_verify": 30.16e6}   # config 3; profiles/config3_step_hbm_bytes.txt
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
@@ -41,6 +44,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload config 1..5 (3 = the metric's shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rotate", action="store_true", help="one replica only (cache-resident inputs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three device copies of 256 MiB (a known size to scale rocprofv3 byte counters by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 "
@@ -94,6 +99,14 @@ def main():
     knn_ms = ev[0].elapsed_time(ev[1]) / knn_reps
     del knn_ws
 
+    if args.calibrate_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     attn_bytes, verify_bytes = algorithmic_bytes(cfg, n_parents)
     step_bytes = attn_bytes + verify_bytes
     R = 1 if args.no_rotate else max(2, int(np.ceil(512e6 / step_bytes)))
@@ -135,35 +148,89 @@ def main():
         attention(d)
         verify(d)
 
-    # ---- timed region: W warm-up steps, then exactly K steps between synchronisations
-    for i in range(args.warmup):
+    # ---- launch path: HIP graphs (one with a step on every replica, one per replica for the
+    # remainder), captured after an eager warm-up; eager launches if capture is not available
+    for i in range(max(R, 3)):
         step(i)
     torch.cuda.synchronize()
+    launch = "hipgraph"
+    try:
+        side = torch.cuda.Stream()
+        def capture(fn):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                global_stream[0] = side
+                with torch.cuda.graph(g, stream=side):
+                    fn()
+                global_stream[0] = torch.cuda.current_stream()
+            return g
+        global_stream = [stream]
+        def attention_s(d):
+            lpp.lpp_tree_attention(tree, dtype, d["q"], d["kc"], d["vc"], d["kt"], d["vt"], None,
+                                   B, H, S, Dh, 0.0, d["out_attn"], attn_ws, global_stream[0])
+        def verify_s(d):
+            lpp.lpp_relaxed_verify(tree, d["target_logits"], d["drafter_logits"], cfg.ldv, cfg.vocab_offset, V, B,
+                                   d["tokens"], neigh, k, k, cfg.lam, d["u_accept"], d["u_final"], d["vout"],
+                                   ver_ws, global_stream[0])
+        g_all = capture(lambda: [(attention_s(d), verify_s(d)) for d in reps])
+        g_one = [capture(lambda d=d: (attention_s(d), verify_s(d))) for d in reps]
+        g_attn = capture(lambda: [attention_s(d) for d in reps])
+        g_ver = capture(lambda: [verify_s(d) for d in reps])
+        torch.cuda.synchronize()
+
+        def run_steps(n):
+            for _ in range(n // R):
+                g_all.replay()
+            for i in range(n % R):
+                g_one[i].replay()
+
+        def run_kernel(g, n):          # n launches of one kernel, R per replay
+            for _ in range(n // R):
+                g.replay()
+            return (n // R) * R
+    except Exception as e:             # pragma: no cover - depends on the runtime
+        launch = "eager (graph capture failed: %s)" % type(e).__name__
+        g_attn = g_ver = None
+
+        def run_steps(n):
+            for i in range(n):
+                step(i)
+
+        def run_kernel(g, n):
+            fn = attention if run_kernel.which == "a" else verify
+            for i in range(n):
+                fn(reps[i % R])
+            return n
+
+    # ---- timed region: W warm-up steps, then exactly K steps between synchronisations
+    run_steps(args.warmup)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
+    run_steps(args.steps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     steps_per_s = 1e3 / ms_per_step
     mean_accept = float(torch.stack([d["vout"]["accept_len"] for d in reps]).float().mean().item())
 
-    # ---- per-call device time over the same K steps (HIP events on the launch stream)
-    def device_ms(fn):
+    # ---- per-kernel device time: HIP events on the launch stream around back-to-back launches of
+    # one kernel over the rotating replicas (includes the gap between dependent launches)
+    def device_ms(which):
+        run_kernel.which = which
+        g = g_attn if which == "a" else g_ver
         ev[0].record()
-        for i in range(args.steps):
-            fn(reps[i % R])
+        n = run_kernel(g, max(args.steps, R))
         ev[1].record()
         torch.cuda.synchronize()
-        return ev[0].elapsed_time(ev[1]) / args.steps
+        return ev[0].elapsed_time(ev[1]) / n
 
-    attn_ms = device_ms(attention)
-    verify_ms = device_ms(verify)
+    attn_ms = device_ms("a")
+    verify_ms = device_ms("v")
     kern = {"tree_attention": {"ms": attn_ms, "bytes": attn_bytes, "GBs": attn_bytes / attn_ms / 1e6},
             "relaxed_verify": {"ms": verify_ms, "bytes": verify_bytes, "GBs": verify_bytes / verify_ms / 1e6}}
     dom = max(kern, key=lambda n: kern[n]["ms"])
     roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": kern[dom]["GBs"] / HBM_PEAK_GBS, "traffic": None,
+                "frac": kern[dom]["GBs"] / HBM_PEAK_GBS, "traffic": TRAFFIC.get(dom) if cfg.idx == 3 else None,
                 "per_call": {n: {"ms": round(v["ms"], 5), "algorithmic_bytes": v["bytes"],
                                  "GBs": round(v["GBs"], 1), "frac": round(v["GBs"] / HBM_PEAK_GBS, 4)}
                              for n, v in kern.items()},
@@ -179,14 +246,17 @@ def main():
         from oracle import relaxed_verify, tree_attention
         neigh_h = neigh.cpu().numpy()           # input table for the oracle's verify step
         nb = min(B, 1 if cfg.idx >= 5 else B)
-        t0 = time.perf_counter()
-        tree_attention(att["q"][:nb], att["kc"][:nb], att["vc"][:nb], att["kt"][:nb], att["vt"][:nb], parent)
-        relaxed_verify(parent, ver["target_logits"][:nb], ver["drafter_logits"][:nb], cfg.vocab_offset, V,
-                       ver["tokens"][:nb], neigh_h, k, cfg.lam, ver["u_accept"][:nb], ver["u_final"][:nb])
-        dt = time.perf_counter() - t0
-        cpu = {"value": (nb / B) / dt, "unit": "steps/s", "cores": len(os.sched_getaffinity(0)),
-               "kind": "oracle", "sample": f"{nb} of {B} batch items of one step, scaled to a full step "
-               f"({dt:.2f} s of CPU work; numpy float64, BLAS threads as configured by the host)"}
+        n_rep, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and n_rep < 500:     # about 10 s of CPU work
+            t0 = time.perf_counter()
+            tree_attention(att["q"][:nb], att["kc"][:nb], att["vc"][:nb], att["kt"][:nb], att["vt"][:nb], parent)
+            relaxed_verify(parent, ver["target_logits"][:nb], ver["drafter_logits"][:nb], cfg.vocab_offset, V,
+                           ver["tokens"][:nb], neigh_h, k, cfg.lam, ver["u_accept"][:nb], ver["u_final"][:nb])
+            t_cpu += time.perf_counter() - t0
+            n_rep += 1
+        cpu = {"value": n_rep * (nb / B) / t_cpu, "unit": "steps/s", "cores": len(os.sched_getaffinity(0)),
+               "kind": "oracle", "sample": f"{nb} of {B} batch items of one step, {n_rep} times "
+               f"({t_cpu:.1f} s of CPU work; numpy float64, BLAS threads as configured by the host)"}
 
     out = {"metric": "tree_verify_steps_per_sec", "value": steps_per_s, "unit": "steps/s",
            "verified_nodes_per_sec": steps_per_s * B * cfg.N,
@@ -195,7 +265,8 @@ def main():
            "dtype": "f32", "dtype_note": "verify: f32; attention: %s inputs on MFMA, f32 softmax/accumulate" % cfg.kv_dtype,
            "data": "synthetic",
            "config": {"workload": f"config {cfg.idx} ({cfg.name}): B={B} H={H}x{Dh} S={S} M={M} V={V} k={k} "
-                                  f"lambda={cfg.lam}", "replicas_rotated": R, "mean_accept_len": mean_accept},
+                                  f"lambda={cfg.lam}", "replicas_rotated": R, "mean_accept_len": mean_accept,
+                      "launch": launch},
            "roofline": roofline, "cpu_baseline": cpu, "knn_build": knn}
     print(json.dumps(out))
 
