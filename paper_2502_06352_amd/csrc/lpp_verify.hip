@@ -32,6 +32,7 @@
 namespace {
 
 constexpr int kMaxStage = 8;       // neighbour lists of the first children kept in LDS
+constexpr int kStageSmall = 4;     // ... when two rows per compute unit have to fit
 constexpr float kLog2e = 1.44269504088896340736f;
 
 // Build with -DLPP_VERIFY_TIMESTAMPS to record per-block phase times (100 MHz counter)
@@ -102,13 +103,15 @@ __device__ __forceinline__ float wave_inclusive_scan(float v) {
 // be out of order by a rounding; a running maximum puts them back in order.
 __device__ __forceinline__ float wave_monotone_scan(float v) {
   v = wave_inclusive_scan(v);
-  v = fmaxf(v, dpp_or<0x111, 0xf>(0.f, v));
-  v = fmaxf(v, dpp_or<0x112, 0xf>(0.f, v));
-  v = fmaxf(v, dpp_or<0x114, 0xf>(0.f, v));
-  v = fmaxf(v, dpp_or<0x118, 0xf>(0.f, v));
-  v = fmaxf(v, dpp_or<0x142, 0xa>(0.f, v));
-  v = fmaxf(v, dpp_or<0x143, 0xc>(0.f, v));
-  return v;
+  // (non-negative floats order like their bit patterns: an integer maximum, which the DPP forms take directly)
+  uint32_t u = __float_as_uint(v);
+  u = max(u, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)u, 0x111, 0xf, 0xf, false));
+  u = max(u, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)u, 0x112, 0xf, 0xf, false));
+  u = max(u, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)u, 0x114, 0xf, 0xf, false));
+  u = max(u, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)u, 0x118, 0xf, 0xf, false));
+  u = max(u, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)u, 0x142, 0xa, 0xf, false));
+  u = max(u, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)u, 0x143, 0xc, 0xf, false));
+  return __uint_as_float(u);
 }
 __device__ __forceinline__ float wave_prev_lane(float v, float first) {   // lane i <- lane i-1
   return dpp_or<0x138, 0xf>(first, v);                                      // wave_shr:1
@@ -296,12 +299,12 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
 #pragma unroll
   for (int ci = 0; ci < kMaxStage; ++ci) {
     crow[ci] = first_child + ci;
-    if (!a.consecutive && ci < nst) crow[ci] = a.child_idx[cp0 + ci];
+    if (!a.consecutive && ci < nchild) crow[ci] = a.child_idx[cp0 + ci];
   }
 #pragma unroll
   for (int ci = 0; ci < kMaxStage; ++ci) {
     stok[ci] = 0;
-    if (ci < nst) stok[ci] = min(max(a.tokens[nodebase + crow[ci]], 0), V - 1);
+    if (ci < nchild) stok[ci] = min(max(a.tokens[nodebase + crow[ci]], 0), V - 1);
   }
   int my_tok = 0, my_child = 0;
 #pragma unroll
@@ -325,13 +328,14 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   }
 
   __builtin_amdgcn_sched_barrier(0);   // every load above is issued before anything below waits
+  const bool full_row = V == NT * NCH * 4;   // no token of the block's range lies past the vocabulary
 
   // ---- softmax statistics of both rows (Sec. 2 notation: q target, p drafter; T = 1)
   float mt = -INFINITY, md = -INFINITY;
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    tv[j] = mask_logits4(tv[j], 4 * (tid + NT * j), V);
-    dv[j] = mask_logits4(dv[j], 4 * (tid + NT * j), nchild > 0 ? V : 0);
+    if (!full_row) tv[j] = mask_logits4(tv[j], 4 * (tid + NT * j), V);
+    if (!full_row || nchild == 0) dv[j] = mask_logits4(dv[j], 4 * (tid + NT * j), nchild > 0 ? V : 0);
     mt = fmaxf(mt, fmaxf(fmaxf(tv[j].x, tv[j].y), fmaxf(tv[j].z, tv[j].w)));
     md = fmaxf(md, fmaxf(fmaxf(dv[j].x, dv[j].y), fmaxf(dv[j].z, dv[j].w)));
   }
@@ -390,7 +394,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     for (int e = 0; e < 4; ++e) p_reg[j][e] = p_reg[j][e] * inv_sd;
 
   if (P == 0 && tid == 0) {  // row 0 is no drafted node: defined outputs
-    a.ws_decision[nodebase] = 0;
+    __hip_atomic_store(&a.ws_decision[nodebase], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (a.decision) a.decision[nodebase] = 0;
     if (a.ratio) a.ratio[nodebase] = 0.f;
     if (a.mass) a.mass[nodebase] = 0.f;
@@ -473,7 +477,9 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       const float qt = rt * rs, m = s_mass * rs;
       const float pt = exp2_fma(s_dlog[ci], md2) * inv_sd;
       const int dec = (s_u[ci] * pt < m) ? 1 : 0;               // u < min(1, mass / p(x^))
-      a.ws_decision[nodebase + c] = (P << 1) | dec;             // what the walk needs of this node
+      // what the walk needs of this node: a device-scope store, visible to every compute unit
+      // once it has completed (no cache write-back needed before the ticket below)
+      __hip_atomic_store(&a.ws_decision[nodebase + c], (P << 1) | dec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
       if (a.ratio) a.ratio[nodebase + c] = m / pt;
       if (a.mass) a.mass[nodebase + c] = m;
@@ -483,7 +489,8 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     }
     // outcome "rejected": keep the positive part of (r' - p); its sum is the new normaliser
     // (Eq. 2).  Product and difference are rounded separately: a drafter equal to the target
-    // then leaves exactly nothing.
+    // then leaves exactly nothing.  (r' rs - p <= 1, so clamping to [0, 1] is the positive part:
+    // it folds into the subtraction.)
     float4 rv[NCH];
     float z = 0.f;
 #pragma unroll
@@ -491,10 +498,10 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       float4* own = reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]);
       rv[j] = *own;
       float4 res;
-      res.x = fmaxf(rv[j].x * rs - p_reg[j][0], 0.f);
-      res.y = fmaxf(rv[j].y * rs - p_reg[j][1], 0.f);
-      res.z = fmaxf(rv[j].z * rs - p_reg[j][2], 0.f);
-      res.w = fmaxf(rv[j].w * rs - p_reg[j][3], 0.f);
+      res.x = __builtin_amdgcn_fmed3f(rv[j].x * rs - p_reg[j][0], 0.f, 1.f);
+      res.y = __builtin_amdgcn_fmed3f(rv[j].y * rs - p_reg[j][1], 0.f, 1.f);
+      res.z = __builtin_amdgcn_fmed3f(rv[j].z * rs - p_reg[j][2], 0.f, 1.f);
+      res.w = __builtin_amdgcn_fmed3f(rv[j].w * rs - p_reg[j][3], 0.f, 1.f);
       z += (res.x + res.y) + (res.z + res.w);
       *own = res;
     }
@@ -596,22 +603,26 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   LPP_TS(29);
   int ticket = 0;
   if (lane == 0) {
-    a.ws_final[nodebase + P] = x;
+    __hip_atomic_store(&a.ws_final[nodebase + P], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (a.final_all) a.final_all[nodebase + P] = x;
     if (a.counters) {
-      __threadfence();
-      ticket = atomicAdd(&a.counters[b], 1);
+      // every store of this row's decisions and draw was issued by this lane: once they have
+      // completed they are visible device-wide, and only then the ticket is taken
+      __atomic_signal_fence(__ATOMIC_SEQ_CST);
+      __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+      __atomic_signal_fence(__ATOMIC_SEQ_CST);
+      ticket = __hip_atomic_fetch_add(&a.counters[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
   if (!a.counters) return;
   ticket = __builtin_amdgcn_readfirstlane(ticket);
   if (ticket != a.M - 1) return;
-  // ---- this row finished last for item b: every decision of the item is visible
-  __threadfence();
+  // ---- this row finished last for item b: every decision of the item is visible (the walk reads
+  // them with device-scope loads)
   int* s_walk = reinterpret_cast<int*>(smem);     // r is dead
   walk_wave(a.ws_decision + nodebase, a.ws_final + nodebase, a.M, a.depth, lane, s_walk, s_walk + a.M,
             a.accept_len + b, a.path + (int64_t)b * a.depth, a.final_token + b);
-  if (lane == 0) a.counters[b] = 0;    // ready for the next call
+  if (lane == 0) __hip_atomic_store(&a.counters[b], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);    // ready for the next call
   LPP_TS(30);
 }
 
@@ -670,7 +681,10 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
   a.target = target_logits; a.drafter = drafter_logits; a.ldv = ldv; a.off = vocab_offset;
   a.V = V; a.M = tree->M; a.B = B; a.kstride = kstride; a.k = k; a.lambda = lambda;
   a.depth = tree->depth > 0 ? tree->depth : 1;
-  a.nstage = std::min<int32_t>(tree->max_children, kMaxStage);
+  // Staged lists cost LDS.  When there are several rows per compute unit, two rows resident at
+  // once (one computing while the other's loads are in flight) are worth more than staging the
+  // lists of a row's fifth and later children: those children read their lists from global memory.
+  a.nstage = std::min<int32_t>(tree->max_children, (int64_t)B * tree->M > 2 * 256 ? kStageSmall : kMaxStage);
   a.tokens = tokens; a.neigh = neigh; a.u_accept = u_accept; a.u_final = u_final;
   a.decision = out->decision; a.ratio = out->ratio; a.mass = out->mass; a.n_agg = out->n_agg;
   a.q_tok = out->q_tok; a.p_tok = out->p_tok; a.final_all = out->final_tok_all;
