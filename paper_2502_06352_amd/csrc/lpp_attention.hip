@@ -115,6 +115,7 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   constexpr int WROWS = NT * 16;     // rows of a wave
   constexpr int ROWS = RW * WROWS;   // rows of the block
   constexpr int OPITCH = DH + 4;     // floats per row of the merge buffer
+  constexpr int MS = (KW * NT * 16 * (DH + 4) * 4 <= 96 * 1024) ? KW : KW / 2;   // merge slots
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_ticket;
 
@@ -349,7 +350,7 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
     uint64_t vis[NT];
     int gx = c0 + kw;                                 // next general group of this wave
     if (GF >= 1) {
-      constexpr int D = DH == 64 ? 4 : 2;
+      constexpr int D = (DH == 64 && NT <= 2) ? 4 : 2;
       Stage<DH> st[D];
       const bool pre = gx < gend;
       if (pre) { visibility(vis, gx); load_any(cst, gx); }
@@ -392,8 +393,8 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
 #endif
   __syncthreads();   // every wave is done with its V tiles: the buffer is reused below
   LPP_ATS(2);
-  float* s_o = reinterpret_cast<float*>(smem);                  // [W][ROWS][OPITCH]
-  float* s_m = s_o + W * ROWS * OPITCH;                         // [W][ROWS], then the block's: [ROWS]
+  float* s_o = reinterpret_cast<float*>(smem);                  // [MS][ROWS][OPITCH]
+  float* s_m = s_o + MS * ROWS * OPITCH;                         // [W][ROWS], then the block's: [ROWS]
   float* s_l = s_m + (W + 1) * ROWS;                            // [W][ROWS], then the block's: [ROWS]
   const int r0 = rw * WROWS;                                    // my first row inside the block
   if (g4 == 0) {
@@ -404,6 +405,7 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
     }
   }
   __syncthreads();
+  float fscale[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int col = r0 + nt * 16 + l16;
@@ -414,13 +416,30 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
 #pragma unroll
     for (int w = 0; w < KW; ++w)
       ll += __builtin_amdgcn_exp2f(s_m[(rw * KW + w) * ROWS + col] - mm) * s_l[(rw * KW + w) * ROWS + col];
-    const float f = __builtin_amdgcn_exp2f(m_ref[nt] - mm);
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      float4* dst = reinterpret_cast<float4*>(&s_o[(kw * ROWS + col) * OPITCH + dt * 16 + 4 * g4]);
-      *dst = make_float4(oacc[dt][nt][0] * f, oacc[dt][nt][1] * f, oacc[dt][nt][2] * f, oacc[dt][nt][3] * f);
-    }
+    fscale[nt] = __builtin_amdgcn_exp2f(m_ref[nt] - mm);
     if (kw == 0 && g4 == 0) { s_m[W * ROWS + col] = mm; s_l[W * ROWS + col] = ll; }
+  }
+  // MS slots of [ROWS][OPITCH] floats: with fewer slots than waves the upper waves park first and
+  // the lower ones add themselves on top
+#pragma unroll
+  for (int round = (MS == KW ? 1 : 0); round < 2; ++round) {
+    if (round == 1 && MS != KW) __syncthreads();
+    const bool mine = round == 0 ? kw >= MS : kw < MS;
+    if (mine) {
+      const int sl = kw % MS;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int col = r0 + nt * 16 + l16;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          float4* dst = reinterpret_cast<float4*>(&s_o[(sl * ROWS + col) * OPITCH + dt * 16 + 4 * g4]);
+          float4 v = make_float4(oacc[dt][nt][0] * fscale[nt], oacc[dt][nt][1] * fscale[nt],
+                                 oacc[dt][nt][2] * fscale[nt], oacc[dt][nt][3] * fscale[nt]);
+          if (round == 1 && MS != KW) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+          *dst = v;
+        }
+      }
+    }
   }
   __syncthreads();
   LPP_ATS(3);
@@ -435,7 +454,7 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
     if (m >= M || !live) continue;
     float4 v = *reinterpret_cast<const float4*>(&s_o[r * OPITCH + c4 * 4]);
 #pragma unroll
-    for (int w = 1; w < KW; ++w) {
+    for (int w = 1; w < MS; ++w) {
       const float4 o = *reinterpret_cast<const float4*>(&s_o[(w * ROWS + r) * OPITCH + c4 * 4]);
       v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
     }
@@ -611,8 +630,16 @@ struct AttnPlan {
 AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh) {
   AttnPlan p;
   p.mtiles = (tree->M + 15) / 16;
-  p.nt = p.mtiles == 1 ? 1 : 2;
-  p.msplits = (p.mtiles + p.nt - 1) / p.nt;
+  // Up to 64 rows: two tiles per wave and one or two blocks per head (enough blocks to fill the
+  // chip at small batch).  More rows: up to five tiles per wave, so that as few blocks as possible
+  // stream the same K/V out of L2.
+  if (p.mtiles <= 4 || Dh != 64) {
+    p.nt = p.mtiles == 1 ? 1 : 2;
+    p.msplits = (p.mtiles + p.nt - 1) / p.nt;
+  } else {
+    p.msplits = (p.mtiles + 4) / 5;
+    p.nt = (p.mtiles + p.msplits - 1) / p.msplits;
+  }
   p.kw = 8;
   const int G = (S + 31) / 32 + (tree->M + 31) / 32;
   const int blocks_bh = B * H * p.msplits;
@@ -624,7 +651,8 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh) {
   p.nsplit = ns;
   const int rows = p.nt * 16;
   const size_t vt = (size_t)p.kw * 2 * 32 * (Dh * 2 + 32);
-  const size_t mg = ((size_t)p.kw * rows * (Dh + 4) + 2 * (p.kw + 1) * rows) * sizeof(float);
+  const int ms = (size_t)p.kw * rows * (Dh + 4) * 4 <= 96 * 1024 ? p.kw : p.kw / 2;
+  const size_t mg = ((size_t)ms * rows * (Dh + 4) + 2 * (p.kw + 1) * rows) * sizeof(float);
   p.lds = vt > mg ? vt : mg;
   return p;
 }
@@ -710,9 +738,15 @@ extern "C" int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype, const
 #define LPP_ATTN(DHV)                                                        \
   do {                                                                       \
     if (p.nt == 1) return launch_bf16<DHV, 1, 1, 8>(a, p, s);                \
-    return launch_bf16<DHV, 2, 1, 8>(a, p, s);                               \
+    if (p.nt == 2) return launch_bf16<DHV, 2, 1, 8>(a, p, s);                \
   } while (0)
-  if (Dh == 64) LPP_ATTN(64);
+  if (Dh == 64) {
+    LPP_ATTN(64);
+    if (p.nt == 3) return launch_bf16<64, 3, 1, 8>(a, p, s);
+    if (p.nt == 4) return launch_bf16<64, 4, 1, 8>(a, p, s);
+    return launch_bf16<64, 5, 1, 8>(a, p, s);
+  }
   LPP_ATTN(128);
+  return LPP_EUNSUPPORTED;
 #undef LPP_ATTN
 }
