@@ -102,7 +102,7 @@ int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, int32_t k,
  *   out       [device] float32 [B, H, M, Dh]
  * Softmax and accumulation are float32; bf16 inputs are multiplied on the matrix
  * cores.  Errors: LPP_EINVAL (null, B/H/S/Dh < 1 -- S = 0 is allowed), LPP_EUNSUPPORTED
- * (Dh not 64 or 128, dtype unknown), LPP_ENOWORKSPACE, LPP_EHIP.
+ * (Dh not 64 or 128, dtype unknown, LPP_F32 with S + M > 36864), LPP_ENOWORKSPACE, LPP_EHIP.
  */
 size_t  lpp_tree_attention_workspace(const lpp_tree* tree, int32_t B, int32_t H,
                                      int32_t S, int32_t Dh);

@@ -21,7 +21,7 @@
 // partials go through the workspace and the block that finishes last adds them up
 // in split order.
 //
-// fp32 path: a plain wave-per-row kernel for small shapes (no matrix cores).
+// fp32 path: a plain two-pass kernel, one block per row, for small shapes (no matrix cores).
 #include <math.h>
 #include <stdlib.h>
 
@@ -563,57 +563,90 @@ struct AttnArgsF32 {
   float* out;
 };
 
+// One block per (tree row, batch*head).  Pass 1: one key per thread, score = scale <q, k>, masked
+// keys dropped, block-wide maximum and sum of exp.  Pass 2: lanes split Dh, waves split the keys,
+// weights come from LDS.  Every load is independent of the previous one, so they overlap.
 __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
-  __shared__ float s_m[4], s_l[4];
+  extern __shared__ __align__(16) float s_p[];       // [seq + M] scores, then weights
+  __shared__ __align__(16) float s_q[128];
+  __shared__ float s_red[2][4];
   __shared__ float s_acc[4][128];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = blockIdx.x, bh = blockIdx.y, b = bh / a.H;
   const int Dh = a.Dh, M = a.M, S = a.S;
   // (branch-free: with no seq_len array the load goes to a valid dummy address)
   const int32_t* slp = a.seq_len ? a.seq_len + b : reinterpret_cast<const int32_t*>(a.q);
   const int slv = *slp;
   const int seq = a.seq_len ? min(max(slv, 0), S) : S;
-  const float* qrow = a.q + ((int64_t)bh * M + m) * Dh;
-  const float q0 = lane < Dh ? qrow[lane] : 0.f;
-  const float q1 = lane + 64 < Dh ? qrow[lane + 64] : 0.f;
-  float mx = -INFINITY, l = 0.f, acc0 = 0.f, acc1 = 0.f;
   const int nkeys = seq + M;
-  for (int j = wave; j < nkeys; j += 4) {
-    const float* kr; const float* vr;
-    if (j < seq) {
-      kr = a.kc + ((int64_t)bh * S + j) * Dh; vr = a.vc + ((int64_t)bh * S + j) * Dh;
-    } else {
-      const int t = j - seq;
-      if (!((a.anc[(int64_t)m * a.words + (t >> 6)] >> (t & 63)) & 1ull)) continue;   // not an ancestor
-      kr = a.kt + ((int64_t)bh * M + t) * Dh; vr = a.vt + ((int64_t)bh * M + t) * Dh;
+  if (tid < Dh) s_q[tid] = a.q[((int64_t)bh * M + m) * Dh + tid];
+  __syncthreads();
+
+  float mx = -INFINITY;
+  for (int j = tid; j < nkeys; j += 256) {
+    float sc = -INFINITY;
+    const int t = j - seq;
+    const bool on = j < seq || ((a.anc[(int64_t)m * a.words + (t >> 6)] >> (t & 63)) & 1ull);
+    if (on) {
+      const float* kr = j < seq ? a.kc + ((int64_t)bh * S + j) * Dh : a.kt + ((int64_t)bh * M + t) * Dh;
+      float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
+      for (int c = 0; c < Dh; c += 4) {
+        const float4 kv = *reinterpret_cast<const float4*>(kr + c);
+        const float4 qv = *reinterpret_cast<const float4*>(s_q + c);
+        d0 += qv.x * kv.x; d1 += qv.y * kv.y; d2 += qv.z * kv.z; d3 += qv.w * kv.w;
+      }
+      sc = ((d0 + d1) + (d2 + d3)) * a.scale;
     }
-    float part = (lane < Dh ? q0 * kr[lane] : 0.f) + (lane + 64 < Dh ? q1 * kr[lane + 64] : 0.f);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
-    const float s = part * a.scale;
-    const float mn = fmaxf(mx, s);
-    const float alpha = expf(mx - mn), p = expf(s - mn);
-    mx = mn;
-    l = l * alpha + p;
-    acc0 = acc0 * alpha + (lane < Dh ? p * vr[lane] : 0.f);
-    acc1 = acc1 * alpha + (lane + 64 < Dh ? p * vr[lane + 64] : 0.f);
+    s_p[j] = sc;
+    mx = fmaxf(mx, sc);
   }
-  if (lane == 0) { s_m[wave] = mx; s_l[wave] = l; }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  if (lane == 0) s_red[0][wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(s_red[0][0], s_red[0][1]), fmaxf(s_red[0][2], s_red[0][3]));   // finite: a row sees itself
+  float l = 0.f;
+  for (int j = tid; j < nkeys; j += 256) {
+    const float sc = s_p[j];
+    const float p = sc == -INFINITY ? 0.f : expf(sc - mx);
+    s_p[j] = p;
+    l += p;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+  if (lane == 0) s_red[1][wave] = l;
+  __syncthreads();
+  l = (s_red[1][0] + s_red[1][1]) + (s_red[1][2] + s_red[1][3]);
+
+  // (loads are unconditional and eight keys deep; a key with weight 0 -- masked or underflowed --
+  // contributes an exact 0 whatever its V row holds)
+  float acc0 = 0.f, acc1 = 0.f;
+  const bool hi = lane + 64 < Dh;
+  for (int j0 = wave; j0 < nkeys; j0 += 32) {
+    float pj[8], v0[8], v1[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = min(j0 + 4 * u, nkeys - 1);
+      pj[u] = j0 + 4 * u < nkeys ? s_p[j] : 0.f;
+      const float* vr = j < seq ? a.vc + ((int64_t)bh * S + j) * Dh : a.vt + ((int64_t)bh * M + (j - seq)) * Dh;
+      v0[u] = vr[lane];
+      v1[u] = hi ? vr[lane + 64] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      acc0 += pj[u] != 0.f ? pj[u] * v0[u] : 0.f;
+      acc1 += pj[u] != 0.f ? pj[u] * v1[u] : 0.f;
+    }
+  }
   s_acc[wave][lane] = acc0;
   s_acc[wave][lane + 64] = acc1;
   __syncthreads();
   if (wave == 0) {
-    float mm = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
-    float ll = 0.f, o0 = 0.f, o1 = 0.f;
-    for (int w = 0; w < 4; ++w) {
-      const float f = s_m[w] == -INFINITY ? 0.f : expf(s_m[w] - mm);
-      ll += f * s_l[w];
-      o0 += f * s_acc[w][lane];
-      o1 += f * s_acc[w][lane + 64];
-    }
+    const float o0 = (s_acc[0][lane] + s_acc[1][lane]) + (s_acc[2][lane] + s_acc[3][lane]);
+    const float o1 = (s_acc[0][lane + 64] + s_acc[1][lane + 64]) + (s_acc[2][lane + 64] + s_acc[3][lane + 64]);
     float* orow = a.out + ((int64_t)bh * M + m) * Dh;
-    if (lane < Dh) orow[lane] = o0 / ll;
-    if (lane + 64 < Dh) orow[lane + 64] = o1 / ll;
+    if (lane < Dh) orow[lane] = o0 / l;
+    if (lane + 64 < Dh) orow[lane + 64] = o1 / l;
   }
 }
 
@@ -711,7 +744,15 @@ extern "C" int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype, const
     a.q = (const float*)q; a.kc = (const float*)k_cache; a.vc = (const float*)v_cache;
     a.kt = (const float*)k_tree; a.vt = (const float*)v_tree; a.seq_len = seq_len; a.anc = tree->d_anc;
     a.B = B; a.H = H; a.S = S; a.M = tree->M; a.words = tree->words; a.Dh = Dh; a.scale = scale; a.out = out;
-    hipLaunchKernelGGL(tree_attn_f32_kernel, dim3((unsigned)tree->M, (unsigned)(B * H)), dim3(256), 0, s, a);
+    static size_t attr_lds = 48 * 1024;
+    const size_t lds = (size_t)(S + tree->M) * sizeof(float);
+    if (lds > 144 * 1024) return LPP_EUNSUPPORTED;     // the scores of one row are kept in LDS
+    if (lds > attr_lds) {
+      LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(tree_attn_f32_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+      attr_lds = lds;
+    }
+    hipLaunchKernelGGL(tree_attn_f32_kernel, dim3((unsigned)tree->M, (unsigned)(B * H)), dim3(256), lds, s, a);
     LPP_HIP_TRY(hipGetLastError());
     return LPP_OK;
   }
