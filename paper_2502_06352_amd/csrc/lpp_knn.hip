@@ -31,7 +31,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kBins = 1024;
 constexpr float kBinScale = 512.0f;           // bin = floor((s + 1) * 512), clamped
 constexpr int kSelWaves = 4;
-constexpr int kSelRows = kSelWaves * 16;      // codes per select block
+constexpr int kSelRows = 16;                  // query codes per select block
 constexpr int kRankThreads = 256;
 constexpr int kSlack = 1024;                  // candidate list = k - 1 + slack (rounded)
 
@@ -51,25 +51,32 @@ __global__ void knn_init_kernel(KnnArgs a) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *a.maxnorm = 0u;
 }
 
-// One wave per row: padded copy, norm, max norm.
+// A wave per row, 16 rows per wave: padded copy, norm; one atomic per block for the max norm.
+constexpr int kPackRows = 64;   // rows per block of 4 waves
 __global__ __launch_bounds__(256) void knn_pack_kernel(KnnArgs a) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= a.Vp) return;
-  float ss = 0.f;
-  for (int d = lane; d < a.DP; d += 64) {
-    float v = 0.f;
-    if (row < a.V && d < a.D) v = a.E[(int64_t)row * a.D + d];
-    a.Ep[(int64_t)row * a.DP + d] = v;
-    ss += v * v;
-  }
+  __shared__ float s_max[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float mx = 0.f;
+  for (int i = 0; i < kPackRows / 4; ++i) {
+    const int row = blockIdx.x * kPackRows + 4 * i + wave;
+    if (row >= a.Vp) break;
+    float ss = 0.f;
+    for (int d = lane; d < a.DP; d += 64) {
+      float v = 0.f;
+      if (row < a.V && d < a.D) v = a.E[(int64_t)row * a.D + d];
+      a.Ep[(int64_t)row * a.DP + d] = v;
+      ss += v * v;
+    }
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-  if (lane == 0) {
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
     const float n = sqrtf(ss);
-    a.norms[row] = n;
-    if (row < a.V) atomicMax(a.maxnorm, __float_as_uint(n));
+    if (lane == 0) a.norms[row] = n;
+    if (row < a.V) mx = fmaxf(mx, n);
   }
+  if (lane == 0) s_max[wave] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    atomicMax(a.maxnorm, __float_as_uint(fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]))));
 }
 
 __device__ __forceinline__ int sim_bin(float s) {
@@ -81,63 +88,76 @@ __device__ __forceinline__ int sim_bin(float s) {
 
 // NS4 = float4 loads per lane and code (DP = 16 * NS4).  Contraction slot (step, g)
 // of the 16x16x4 MFMA is dimension 16*(step/4) + 4*g + step%4 on both operands.
+// A block owns 16 query codes; its 4 waves take the code tiles (16 codes each) in turn and share
+// the rows' histograms in LDS, so that a compute unit holds many waves and the latency of the
+// tile loads (served by L2: the codebook is small) is covered.  U tiles are in flight per wave.
 template <int NS4>
 __global__ __launch_bounds__(kSelWaves * 64) void knn_select_kernel(KnnArgs a) {
+  constexpr int U = NS4 <= 2 ? 4 : (NS4 <= 4 ? 2 : 1);
   extern __shared__ uint32_t s_hist[];          // [kSelRows][kBins/2], two 16-bit counts per word
   __shared__ int s_cnt[kSelRows];
+  __shared__ int s_bstar[kSelRows];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l16 = lane & 15, g4 = lane >> 4;
-  const int row0 = blockIdx.x * kSelRows + wave * 16;   // this wave's 16 query codes
+  const int row0 = blockIdx.x * kSelRows;               // the block's 16 query codes
   const int qrow = row0 + l16;                          // the lane's query code (B operand column)
   const int DP = a.DP, V = a.V;
   const int kk = a.k - 1;                               // neighbours besides the code itself
+  const int ntiles = a.Vp / 16;
 
   f32x4 qv[NS4];
 #pragma unroll
   for (int s = 0; s < NS4; ++s)
     qv[s] = *reinterpret_cast<const f32x4*>(a.Ep + (int64_t)qrow * DP + 16 * s + 4 * g4);
 
-  uint32_t* hist = s_hist + (wave * 16) * (kBins / 2);
-  for (int i = lane; i < 16 * (kBins / 2); i += 64) hist[i] = 0u;
-  if (lane < 16) s_cnt[wave * 16 + lane] = 0;
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  for (int i = threadIdx.x; i < kSelRows * (kBins / 2); i += kSelWaves * 64) s_hist[i] = 0u;
+  if (threadIdx.x < kSelRows) s_cnt[threadIdx.x] = 0;
+  __syncthreads();
 
   int bstar = 0;
   for (int phase = 0; phase < 2; ++phase) {
-    for (int c0 = 0; c0 < a.Vp; c0 += 16) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      const float* arow = a.Ep + (int64_t)(c0 + l16) * DP + 4 * g4;
+    for (int t0 = wave; t0 < ntiles; t0 += kSelWaves * U) {
+      f32x4 av[U][NS4];
 #pragma unroll
-      for (int s = 0; s < NS4; ++s) {
-        const f32x4 av = *reinterpret_cast<const f32x4*>(arow + 16 * s);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[0], qv[s][0], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[1], qv[s][1], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[2], qv[s][2], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[3], qv[s][3], acc, 0, 0, 0);
+      for (int u = 0; u < U; ++u) {
+        const int t = min(t0 + kSelWaves * u, ntiles - 1);      // (past the end: a re-read that is not used)
+        const float* arow = a.Ep + (int64_t)(t * 16 + l16) * DP + 4 * g4;
+#pragma unroll
+        for (int s = 0; s < NS4; ++s) av[u][s] = *reinterpret_cast<const f32x4*>(arow + 16 * s);
       }
-      // lane holds sim(code c0 + 4*g4 + r, query qrow), r = 0..3
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int code = c0 + 4 * g4 + r;
-        if (code >= V || code == qrow || qrow >= V) continue;
-        const int bin = sim_bin(acc[r]);
-        if (phase == 0) {
-          atomicAdd(&hist[l16 * (kBins / 2) + (bin >> 1)], (bin & 1) ? 65536u : 1u);
-        } else if (bin >= bstar - 1) {
-          const int pos = atomicAdd(&s_cnt[wave * 16 + l16], 1);
-          if (pos < a.cap) a.cand[(int64_t)qrow * a.cap + pos] = (uint16_t)code;
+      for (int u = 0; u < U; ++u) {
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // two chains: the matrix core stays busy
+#pragma unroll
+        for (int s = 0; s < NS4; ++s) {
+          acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][s][0], qv[s][0], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][s][1], qv[s][1], acc1, 0, 0, 0);
+          acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][s][2], qv[s][2], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][s][3], qv[s][3], acc1, 0, 0, 0);
+        }
+        const f32x4 acc = acc0 + acc1;
+        const int t = t0 + kSelWaves * u;
+        if (t >= ntiles) continue;
+        // lane holds sim(code 16 t + 4*g4 + r, query qrow), r = 0..3
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int code = t * 16 + 4 * g4 + r;
+          if (code >= V || code == qrow || qrow >= V) continue;
+          const int bin = sim_bin(acc[r]);
+          if (phase == 0) {
+            atomicAdd(&s_hist[l16 * (kBins / 2) + (bin >> 1)], (bin & 1) ? 65536u : 1u);
+          } else if (bin >= bstar - 1) {
+            const int pos = atomicAdd(&s_cnt[l16], 1);
+            if (pos < a.cap) a.cand[(int64_t)qrow * a.cap + pos] = (uint16_t)code;
+          }
         }
       }
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __syncthreads();
     if (phase == 0) {
-      // b* of each of the wave's 16 rows: highest bin whose count-from-the-top reaches kk
-      for (int r = 0; r < 16; ++r) {
-        const uint32_t* h = hist + r * (kBins / 2);
+      // b* of each row: highest bin whose count-from-the-top reaches kk; a wave takes 4 of the 16 rows
+      for (int r = wave * (kSelRows / kSelWaves); r < (wave + 1) * (kSelRows / kSelWaves); ++r) {
+        const uint32_t* h = s_hist + r * (kBins / 2);
         // lane covers bins [1023 - 16*lane - 15, 1023 - 16*lane], scanned downwards
         int cntv[16];
         int local = 0;
@@ -170,12 +190,16 @@ __global__ __launch_bounds__(kSelWaves * 64) void knn_select_kernel(KnnArgs a) {
           }
           bs = __shfl(found, fl);
         }
-        if (l16 == r) bstar = bs;
+        if (lane == 0) {
+          s_bstar[r] = bs;
+          if (row0 + r < a.Vp) a.bstar[row0 + r] = bs;
+        }
       }
-      if (g4 == 0 && qrow < a.Vp) a.bstar[qrow] = bstar;
+      __syncthreads();
+      bstar = s_bstar[l16];
     }
   }
-  if (lane < 16 && row0 + lane < a.Vp) a.cnt[row0 + lane] = s_cnt[wave * 16 + lane];
+  if (threadIdx.x < kSelRows && row0 + threadIdx.x < a.Vp) a.cnt[row0 + threadIdx.x] = s_cnt[threadIdx.x];
 }
 
 __device__ __forceinline__ uint64_t orderable(double x) {
@@ -341,7 +365,7 @@ KnnLayout knn_layout(int32_t V, int32_t D, int32_t k) {
   KnnLayout L;
   L.DP = 16;
   while (L.DP < D) L.DP <<= 1;             // 16, 32, ..., 256
-  L.Vp = (int32_t)lpp_align_up((size_t)V, kSelRows);
+  L.Vp = (int32_t)lpp_align_up((size_t)V, 64);
   L.cap = cap_for(k);
   size_t o = 0;
   L.o_ep = o;    o += lpp_align_up((size_t)L.Vp * L.DP * sizeof(float), 256);
@@ -399,7 +423,7 @@ extern "C" int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, in
 
   hipLaunchKernelGGL(knn_init_kernel, dim3(1), dim3(64), 0, s, a);
   LPP_HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(knn_pack_kernel, dim3((unsigned)((L.Vp + 3) / 4)), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(knn_pack_kernel, dim3((unsigned)((L.Vp + kPackRows - 1) / kPackRows)), dim3(256), 0, s, a);
   LPP_HIP_TRY(hipGetLastError());
   if (k > 1) {
     int32_t st;
