@@ -137,10 +137,8 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   const int b = (int)div_rc((uint32_t)bh, (uint32_t)a.H, a.rc_H);
   const int M = a.M, S = a.S;
   const int m0 = ms * ROWS + rw * WROWS;       // first row of this wave
-  // (branch-free: with no seq_len array the load goes to a valid dummy address)
-  const int32_t* slp = a.seq_len ? a.seq_len + b : reinterpret_cast<const int32_t*>(a.q);
-  const int slv = *slp;
-  const int seq = a.seq_len ? min(max(slv, 0), S) : S;
+  int seq = S;
+  if (a.seq_len) seq = min(max(a.seq_len[b], 0), S);     // (everything below depends on it anyway)
   const int GC = (seq + 31) >> 5, GT = (M + 31) >> 5, G = GC + GT;
   const int gbeg = (int)div_rc((uint32_t)(split * G), (uint32_t)a.nsplit, a.rc_nsplit);
   const int gend = (int)div_rc((uint32_t)((split + 1) * G), (uint32_t)a.nsplit, a.rc_nsplit);
@@ -338,10 +336,10 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   const std::integral_constant<bool, true> kFull;
   const std::integral_constant<bool, false> kAny;
 
-  // ---- this wave's groups.  Its first general group is fetched before anything else and worked
-  // on while the loads of the full groups are in flight; those go through a ring of D stages: the
-  // loads of the next D - 1 groups are in flight while one is worked on, and a stage is refilled
-  // as soon as it has been consumed.
+  // ---- this wave's groups.  The full groups go through a ring of D stages: the loads of the next
+  // D - 1 groups are in flight while one is worked on, and a stage is refilled as soon as it has
+  // been consumed.  The wave's first general group is fetched before them and worked on while
+  // the ring's first loads are in flight.
   {
     const int h1 = min(gend, GF);                     // full groups: [gbeg, h1)
     const int c0 = max(gbeg, GF);                     // general groups: [c0, gend)
@@ -362,7 +360,7 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
       LPP_ATS(7);
 #pragma unroll
       for (int d = 0; d < D; ++d) load_full(st[d], min(g + d * KW, hl));
-      if (pre) { compute_group(cst, gx, vis, kAny); gx += KW; }
+      if (pre) { compute_group(cst, gx, vis, kAny); gx += KW; }   // while the ring's loads are in flight
       while (g + (D - 1) * KW < h1) {             // whole rounds of the ring
 #pragma unroll
         for (int d = 0; d < D; ++d) {
@@ -574,10 +572,8 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = blockIdx.x, bh = blockIdx.y, b = bh / a.H;
   const int Dh = a.Dh, M = a.M, S = a.S;
-  // (branch-free: with no seq_len array the load goes to a valid dummy address)
-  const int32_t* slp = a.seq_len ? a.seq_len + b : reinterpret_cast<const int32_t*>(a.q);
-  const int slv = *slp;
-  const int seq = a.seq_len ? min(max(slv, 0), S) : S;
+  int seq = S;
+  if (a.seq_len) seq = min(max(a.seq_len[b], 0), S);     // (everything below depends on it anyway)
   const int nkeys = seq + M;
   if (tid < Dh) s_q[tid] = a.q[((int64_t)bh * M + m) * Dh + tid];
   __syncthreads();
