@@ -50,7 +50,7 @@ def _children(parent: np.ndarray) -> List[List[int]]:
 def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits: np.ndarray,
                    vocab_offset: int, V: int, tokens: np.ndarray, neigh: np.ndarray,
                    k: int, lam: float, u_accept: np.ndarray, u_final: np.ndarray,
-                   keep_final_cdf: bool = False) -> Dict[str, np.ndarray]:
+                   keep_final_cdf: bool = False, bound: str = "multiplicative") -> Dict[str, np.ndarray]:
     """target/drafter logits [B,M,ldv]; tokens,u_* [B,M]; neigh [V,>=k] -> dict of outputs.
 
     Outputs (all [B,M] unless noted): decision (uint8), ratio, mass, n_agg,
@@ -58,7 +58,13 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
     final_token [B].  Diagnostics: bound_margin = min_j |cum_j - lam*r(x^)| /
     (lam*r(x^)) over the prefix sums that were compared (inf if none);
     final_cdf [B,M,V] (cumulative, unnormalised) if requested.
+
+    ``bound``: "multiplicative" (Sec. 4, LANTERN++: sum_A r < lam * r(x^)) or "additive" (the
+    earlier LANTERN bound as Sec. 4 prints it: sum_A r < delta, with ``lam`` holding delta).  In
+    both the sum runs over A including x^, and x^ is a member whatever the bound says.
     """
+    if bound not in ("multiplicative", "additive"):
+        raise ValueError("bound must be 'multiplicative' or 'additive'")
     parent = np.asarray(parent)
     B, M = tokens.shape
     kids = _children(parent)
@@ -91,7 +97,7 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
                 for c in kids[P]:
                     t = int(tokens[b, c])
                     nb = neigh[t]
-                    cap = lam * r[t]
+                    cap = lam * r[t] if bound == "multiplicative" else lam
                     vals = r[np.asarray(nb[:k], dtype=np.int64)]
                     vals[0] = r[t]                       # x^ itself is always a member
                     C = np.cumsum(vals)                  # nearest-first prefix sums

@@ -285,3 +285,60 @@ def test_zero_probability_tokens():
     o = _call([-1, 0], np.stack([q, q]), np.stack([p, p]), [0, 0], neigh, 4, 3.0, [0, 0.0], [0.999999, 0.0])
     assert o["n_agg"][0, 1] == 1 and o["mass"][0, 1] == 0 and o["decision"][0, 1] == 0
     assert o["final_tok_all"][0, 0] in (1, 2) and o["final_tok_all"][0, 1] == 1
+
+
+# ------------------------------------------------- additive (LANTERN) bound variant
+def test_additive_bound_brute_force_and_reduction():
+    """sum_A r < delta (Sec. 4, the LANTERN form), x^ always a member: |A| by enumerating all
+    prefixes; delta <= q(x^) leaves A = {x^}, i.e. Eq. 1; and on a single child the additive bound
+    with delta = lambda * q(x^) is the multiplicative one."""
+    g = np.random.default_rng(11)
+    V = 8
+    grew = 0
+    for trial in range(60):
+        q = g.dirichlet(np.ones(V) * 0.5); p = g.dirichlet(np.ones(V))
+        k = int(g.integers(1, V + 1)); t = int(g.integers(V))
+        delta = float(g.uniform(0.02, 0.9))
+        neigh = np.array([[i] + [j for j in g.permutation(V) if j != i] for i in range(V)])
+        args = ([-1, 0], np.stack([q, q]), np.stack([p, p]), [0, t], neigh, k)
+        o = _call(*args, delta, [0, 0.3], [0.1, 0.1], bound="additive")
+        sums = [q[neigh[t][:j]].sum() for j in range(1, k + 1)]
+        ok = [j for j in range(1, k + 1) if all(s < delta for s in sums[1:j])]
+        assert o["n_agg"][0, 1] == max(ok)
+        assert o["mass"][0, 1] == pytest.approx(sums[max(ok) - 1], rel=1e-12)
+        assert o["mass"][0, 1] < delta or o["n_agg"][0, 1] == 1
+        assert o["decision"][0, 1] == (1 if 0.3 < min(1.0, sums[max(ok) - 1] / p[t]) else 0)
+        grew += int(o["n_agg"][0, 1] > 1)
+        # no room under the bound: plain speculative sampling
+        o0 = _call(*args, 0.999 * q[t], [0, 0.3], [0.1, 0.1], bound="additive")
+        assert o0["n_agg"][0, 1] == 1 and o0["ratio"][0, 1] == pytest.approx(q[t] / p[t], rel=1e-12)
+        # the same cap, written both ways
+        lam = float(g.uniform(1.05, 6.0))
+        om = _call(*args, lam, [0, 0.3], [0.1, 0.9], bound="multiplicative")
+        oa = _call(*args, lam * np.float64(q[t]), [0, 0.3], [0.1, 0.9], bound="additive")
+        for name in ("n_agg", "mass", "ratio", "decision", "final_tok_all"):
+            assert np.array_equal(om[name], oa[name]), name
+    assert grew > 10
+
+
+def test_additive_bound_on_workload_rows():
+    cfg = CONFIGS[1]
+    parent = static_tree(cfg.branching, cfg.N)
+    E = make_codebook(cfg)
+    neigh = build_neighbours(E, 64)
+    x = make_verify_inputs(cfg, parent, rho=0.8)
+    prev = None
+    for delta in (1e-4, 0.01, 0.05, 0.3):
+        o = relaxed_verify(parent, x["target_logits"], x["drafter_logits"], 0, cfg.V, x["tokens"],
+                           neigh, 64, delta, x["u_accept"], x["u_final"], bound="additive")
+        for c in range(1, cfg.M):
+            qt, m, na = o["q_tok"][0, c], o["mass"][0, c], o["n_agg"][0, c]
+            assert qt <= m * (1 + 1e-15) and (m < delta or na == 1)
+        first = [c[0] for c in children_lists(parent) if c]
+        if prev is not None:
+            assert np.all(o["mass"][0, first] >= prev - 1e-18)      # monotone in delta where r = q
+        prev = o["mass"][0, first].copy()
+    assert np.any(o["n_agg"][0, 1:] > 1)
+    with pytest.raises(ValueError):
+        relaxed_verify(parent, x["target_logits"], x["drafter_logits"], 0, cfg.V, x["tokens"],
+                       neigh, 64, 0.1, x["u_accept"], x["u_final"], bound="other")
