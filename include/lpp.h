@@ -161,6 +161,19 @@ int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_logits,
                            const float* u_accept, const float* u_final,
                            const lpp_verify_out* out, void* ws, size_t ws_bytes, void* stream);
 
+/* The same step under the additive bound of the earlier LANTERN method, which the paper's Sec. 4
+ * states next to its own:  A = longest nearest-first prefix of B_k(x^) with
+ *     sum_{x in A} r(x) < delta        (x^ always in A; r normalised),
+ * everything else as in lpp_relaxed_verify.  delta <= r(x^) admits no neighbour.  Same arguments,
+ * workspace (lpp_relaxed_verify_workspace) and errors; delta NaN is LPP_EINVAL.
+ */
+int32_t lpp_relaxed_verify_additive(const lpp_tree* tree, const float* target_logits,
+                                    const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                                    int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
+                                    int32_t kstride, int32_t k, float delta,
+                                    const float* u_accept, const float* u_final,
+                                    const lpp_verify_out* out, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,7 +59,8 @@ struct VerifyArgs {
   int64_t ldv;
   int32_t off, V, M, B, kstride, k, depth;
   int32_t nstage;         // child lists whose first pass is staged in LDS (<= kMaxStage)
-  float lambda;
+  float lambda;           // bound factor, or delta when `additive`
+  int32_t additive;       // 0: sum_A r < lambda r(x^)   1: sum_A r < delta
   const int32_t* tokens;
   const int32_t* neigh;
   const float* u_accept;
@@ -408,7 +409,9 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   for (int ci = 0; ci < nchild; ++ci) {
     const int t = s_tok[ci];
     const float rt = r_lds[t];
-    const float cap = a.lambda * rt;                 // bound: sum_A r < lambda * r(x^)   (Sec. 4)
+    // bound: sum_A r < lambda * r(x^)  (Sec. 4), or the additive form sum_A r < delta of the same
+    // section, brought to the scale of the unnormalised r
+    const float cap = a.additive ? a.lambda / rs : a.lambda * rt;
     const int32_t* nrow = a.neigh + (int64_t)t * a.kstride;
 
     // A = longest nearest-first prefix whose running sum stays below the cap.  G(i), the sum
@@ -659,12 +662,13 @@ extern "C" size_t lpp_relaxed_verify_workspace(const lpp_tree* tree, int32_t B, 
   return 2 * lpp_align_up(nodes * sizeof(int32_t), 256);
 }
 
-extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_logits,
-                                      const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
-                                      int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
-                                      int32_t kstride, int32_t k, float lambda, const float* u_accept,
-                                      const float* u_final, const lpp_verify_out* out, void* ws,
-                                      size_t ws_bytes, void* stream) {
+namespace {
+int32_t relaxed_verify_impl(int32_t additive, const lpp_tree* tree, const float* target_logits,
+                            const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                            int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
+                            int32_t kstride, int32_t k, float lambda, const float* u_accept,
+                            const float* u_final, const lpp_verify_out* out, void* ws,
+                            size_t ws_bytes, void* stream) {
   if (!tree || !target_logits || !tokens || !neigh || !u_accept || !u_final || !out) return LPP_EINVAL;
   if (!out->accept_len || !out->path || !out->final_token) return LPP_EINVAL;
   if (tree->M > 1 && !drafter_logits) return LPP_EINVAL;
@@ -679,7 +683,7 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
 
   VerifyArgs a;
   a.target = target_logits; a.drafter = drafter_logits; a.ldv = ldv; a.off = vocab_offset;
-  a.V = V; a.M = tree->M; a.B = B; a.kstride = kstride; a.k = k; a.lambda = lambda;
+  a.V = V; a.M = tree->M; a.B = B; a.kstride = kstride; a.k = k; a.lambda = lambda; a.additive = additive;
   a.depth = tree->depth > 0 ? tree->depth : 1;
   // Staged lists cost LDS.  When there are several rows per compute unit, two rows resident at
   // once (one computing while the other's loads are in flight) are worth more than staging the
@@ -732,4 +736,26 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
     LPP_HIP_TRY(hipGetLastError());
   }
   return LPP_OK;
+}
+}  // namespace
+
+extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_logits,
+                                      const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                                      int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
+                                      int32_t kstride, int32_t k, float lambda, const float* u_accept,
+                                      const float* u_final, const lpp_verify_out* out, void* ws,
+                                      size_t ws_bytes, void* stream) {
+  return relaxed_verify_impl(0, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
+                             kstride, k, lambda, u_accept, u_final, out, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t lpp_relaxed_verify_additive(const lpp_tree* tree, const float* target_logits,
+                                               const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                                               int32_t V, int32_t B, const int32_t* tokens,
+                                               const int32_t* neigh, int32_t kstride, int32_t k, float delta,
+                                               const float* u_accept, const float* u_final,
+                                               const lpp_verify_out* out, void* ws, size_t ws_bytes,
+                                               void* stream) {
+  return relaxed_verify_impl(1, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
+                             kstride, k, delta, u_accept, u_final, out, ws, ws_bytes, stream);
 }

@@ -31,7 +31,7 @@ def sparse_neighbour_table(E, k, tokens, V):
     return neigh
 
 
-def run_verify(tree, x, neigh, cfgV, off, ldv, k, lam, want_all=True, stream=None):
+def run_verify(tree, x, neigh, cfgV, off, ldv, k, lam, want_all=True, stream=None, additive=False):
     B, M = x["tokens"].shape
     depth = max(tree.depth, 1)
     d = {n: dev(x[n]) for n in ("target_logits", "drafter_logits", "tokens", "u_accept", "u_final")}
@@ -46,13 +46,14 @@ def run_verify(tree, x, neigh, cfgV, off, ldv, k, lam, want_all=True, stream=Non
                    q_tok=torch.zeros((B, M), device=DEV), p_tok=torch.zeros((B, M), device=DEV),
                    final_tok_all=torch.full((B, M), -7, dtype=torch.int32, device=DEV))
     ws = torch.empty(lpp.lpp_relaxed_verify_workspace(tree, B, cfgV, k), dtype=torch.uint8, device=DEV)
-    lpp.lpp_relaxed_verify(tree, d["target_logits"], d["drafter_logits"], ldv, off, cfgV, B, d["tokens"], dn,
-                           neigh.shape[1], k, lam, d["u_accept"], d["u_final"], out, ws, stream)
+    call = lpp.lpp_relaxed_verify_additive if additive else lpp.lpp_relaxed_verify
+    call(tree, d["target_logits"], d["drafter_logits"], ldv, off, cfgV, B, d["tokens"], dn,
+         neigh.shape[1], k, lam, d["u_accept"], d["u_final"], out, ws, stream)
     torch.cuda.synchronize()
     return {n: t.cpu().numpy() for n, t in out.items()}
 
 
-def compare_verify(parent, x, neigh, V, off, k, lam, got, rel=1e-4, tie=1e-5, cdf_tol=2e-6):
+def compare_verify(parent, x, neigh, V, off, k, lam, got, rel=1e-4, tie=1e-5, cdf_tol=2e-6, additive=False):
     """Compare every output with the float64 oracle.  Returns a report dict.
 
     Rules: decisions bit-exact unless |u - ratio| < tie (counted); mass / ratio /
@@ -62,7 +63,8 @@ def compare_verify(parent, x, neigh, V, off, k, lam, got, rel=1e-4, tie=1e-5, cd
     final tokens must bracket u*Z in the oracle's float64 CDF within cdf_tol*Z.
     """
     want = relaxed_verify(parent, x["target_logits"], x["drafter_logits"], off, V, x["tokens"], neigh, k, lam,
-                          x["u_accept"], x["u_final"], keep_final_cdf=True)
+                          x["u_accept"], x["u_final"], keep_final_cdf=True,
+                          bound="additive" if additive else "multiplicative")
     kids = children_lists(parent)
     B, M = x["tokens"].shape
     rep = dict(nodes=0, near_tie_decisions=0, nagg_ties=0, skipped_after_tie=0, final_exact=0, final_rows=0,

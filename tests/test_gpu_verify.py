@@ -10,7 +10,7 @@ from gpu_common import run_verify, compare_verify, sparse_neighbour_table
 pytestmark = pytest.mark.gpu
 
 
-def _case(cfg, rho, k=None, lam=None, items=None, topk=0, salt=0):
+def _case(cfg, rho, k=None, lam=None, items=None, topk=0, salt=0, additive=False):
     parent = static_tree(cfg.branching, cfg.N)
     x = make_verify_inputs(cfg, parent, rho=rho, items=items, topk_filter=topk, salt=salt)
     E = make_codebook(cfg)
@@ -18,8 +18,8 @@ def _case(cfg, rho, k=None, lam=None, items=None, topk=0, salt=0):
     lam = cfg.lam if lam is None else lam
     neigh = sparse_neighbour_table(E, k, x["tokens"][:, 1:], cfg.V)
     tree = lpp.Tree(parent)
-    got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, k, lam)
-    rep = compare_verify(parent, x, neigh, cfg.V, cfg.vocab_offset, k, lam, got)
+    got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, k, lam, additive=additive)
+    rep = compare_verify(parent, x, neigh, cfg.V, cfg.vocab_offset, k, lam, got, additive=additive)
     print(f"cfg{cfg.idx} rho={rho} k={k} lam={lam}: {rep} mean accept_len={got['accept_len'].mean():.2f}", flush=True)
     return rep, got
 
@@ -48,6 +48,17 @@ def test_verify_special_cases(k, lam):
     rep, got = _case(cfg, 0.8, k=k, lam=lam)
     if k == 1 or lam <= 1:
         pass  # reduces to plain speculative sampling; the oracle pins that case
+
+
+@pytest.mark.parametrize("idx,delta", [(1, 0.05), (3, 0.01), (3, 0.2), (4, 0.05)])
+def test_verify_additive_bound_parity(idx, delta):
+    """The LANTERN form of the bound (sum over A below delta), same kernel, other cap."""
+    cfg = CONFIGS[idx]
+    rep, got = _case(cfg, 0.8, lam=delta, additive=True)
+    assert rep["nodes"] > 0 and rep["near_tie_decisions"] <= 2 and rep["nagg_ties"] <= 2
+    # and it really is another rule than the multiplicative one with the same number
+    _, mult = _case(cfg, 0.8, lam=delta)
+    assert not np.array_equal(got["n_agg"], mult["n_agg"])
 
 
 def test_verify_topk_filtered_targets_long_prefixes():
