@@ -21,6 +21,11 @@ Functions and what pins them (see tests/test_oracle_*.py):
                     enumeration of the output distribution on tiny vocabularies,
                     Monte Carlo, and the bound invariants of Sec. 4.
 
+  commit_kv         appends the K/V rows of the root and of the accepted path to
+                    the cache (App. A.2).  Pinned by the next step's view: plain
+                    attention over the committed cache equals the tree-masked
+                    attention row of the last accepted node.
+
 Readings the paper does not fix ("parity unpinned": every invariant the paper
 states holds under the alternatives too, so the choice below is the definition):
   * A_{k,lambda} is the longest nearest-first prefix of B_k whose cumulative
@@ -35,3 +40,4 @@ states holds under the alternatives too, so the choice below is the definition):
 from .knn import build_neighbours, similarity_keys            # noqa: F401
 from .attention import tree_attention, ancestor_mask          # noqa: F401
 from .verify import relaxed_verify, softmax64, inverse_cdf    # noqa: F401
+from .commit import commit_kv                                 # noqa: F401
