@@ -174,6 +174,26 @@ int32_t lpp_relaxed_verify_additive(const lpp_tree* tree, const float* target_lo
                                     const float* u_accept, const float* u_final,
                                     const lpp_verify_out* out, void* ws, size_t ws_bytes, void* stream);
 
+/* ---------------------------------------------------------------- commit ---
+ * Appends what the step keeps to the KV cache (paper App. A.2: accepted tokens are kept, the rest
+ * of the tree is discarded).  For item b the rows r_0 = 0 (the root: the last committed token, not
+ * in the cache yet) and r_i = path[b, i-1], 1 <= i <= accept_len[b], of k_tree / v_tree are copied
+ * to cache positions seq_len[b] + i of every head; new_len[b] = seq_len[b] + 1 + accept_len[b].
+ * Rows that would land at or past S are dropped and new_len is capped at S.
+ *   dtype               LPP_F32 or LPP_BF16 (element type of the four K/V tensors)
+ *   k_tree, v_tree      [device] [B, H, M, Dh]
+ *   path, accept_len    [device] int32 [B, depth] / [B], as written by lpp_relaxed_verify
+ *   seq_len             [device] int32 [B] current lengths (clamped to [0, S])
+ *   k_cache, v_cache    [device] [B, H, S, Dh], updated in place
+ *   new_len             [device] int32 [B] out, or NULL; must not be seq_len itself
+ * Errors: LPP_EINVAL (null, sizes < 1, new_len == seq_len), LPP_EUNSUPPORTED (dtype unknown, row
+ * size not a multiple of 16 bytes), LPP_EHIP.
+ */
+int32_t lpp_commit_kv(const lpp_tree* tree, int32_t dtype, const void* k_tree, const void* v_tree,
+                      const int32_t* path, const int32_t* accept_len, const int32_t* seq_len,
+                      int32_t B, int32_t H, int32_t S, int32_t Dh, void* k_cache, void* v_cache,
+                      int32_t* new_len, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -63,6 +63,8 @@ def lib() -> C.CDLL:
                                      C.POINTER(VerifyOut), vp, sz, vp]
     L.lpp_relaxed_verify_additive.restype = i32
     L.lpp_relaxed_verify_additive.argtypes = L.lpp_relaxed_verify.argtypes
+    L.lpp_commit_kv.restype = i32
+    L.lpp_commit_kv.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
     _lib = L
     return L
 
@@ -153,3 +155,10 @@ def lpp_relaxed_verify_additive(tree: Tree, target_logits, drafter_logits, ldv: 
                                              _ptr(u_accept), _ptr(u_final), C.byref(vo), _ptr(ws),
                                              0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
            "lpp_relaxed_verify_additive")
+
+
+def lpp_commit_kv(tree: Tree, dtype: int, k_tree, v_tree, path, accept_len, seq_len, B: int, H: int, S: int,
+                  Dh: int, k_cache, v_cache, new_len, stream=None) -> None:
+    _check(lib().lpp_commit_kv(tree.handle, dtype, _ptr(k_tree), _ptr(v_tree), _ptr(path), _ptr(accept_len),
+                               _ptr(seq_len), B, H, S, Dh, _ptr(k_cache), _ptr(v_cache), _ptr(new_len),
+                               _stream(stream)), "lpp_commit_kv")
