@@ -26,6 +26,10 @@ Functions and what pins them (see tests/test_oracle_*.py):
                     attention over the committed cache equals the tree-masked
                     attention row of the last accepted node.
 
+  sampling_frontend classifier-free guidance + top-k in front of the target softmax
+                    (App. B "Models").  Pinned by special cases (scale 0, equal rows),
+                    a library top-k, counts and brute force.
+
 Readings the paper does not fix ("parity unpinned": every invariant the paper
 states holds under the alternatives too, so the choice below is the definition):
   * A_{k,lambda} is the longest nearest-first prefix of B_k whose cumulative
@@ -41,3 +45,4 @@ from .knn import build_neighbours, similarity_keys            # noqa: F401
 from .attention import tree_attention, ancestor_mask          # noqa: F401
 from .verify import relaxed_verify, softmax64, inverse_cdf    # noqa: F401
 from .commit import commit_kv                                 # noqa: F401
+from .frontend import guided_logits, top_k_filter, sampling_frontend   # noqa: F401
