@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload config 1..5 (3 = the metric's shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rotate", action="store_true", help="one replica only (cache-resident inputs)")
+    ap.add_argument("--frontend", action="store_true",
+                    help="verify through lpp_relaxed_verify_sampled (guidance 3.0 + top-k 2000 fused; reads one more "
+                         "target row set); not the headline configuration")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three device copies of 256 MiB (a known size to scale rocprofv3 byte counters by)")
     args = ap.parse_args()
@@ -77,6 +80,7 @@ def main():
     E = make_codebook(cfg)
     att = make_attention_inputs(cfg)
     ver = make_verify_inputs(cfg, parent, rho=0.8)
+    ver_uncond = make_verify_inputs(cfg, parent, rho=0.0, salt=100) if args.frontend else None
 
     def up(x):
         return torch.from_numpy(np.ascontiguousarray(x)).to(dev)
@@ -108,6 +112,8 @@ def main():
         del src, dst
 
     attn_bytes, verify_bytes = algorithmic_bytes(cfg, n_parents)
+    if args.frontend:
+        verify_bytes += 4 * B * V * M            # the null-conditioned target rows
     step_bytes = attn_bytes + verify_bytes
     R = 1 if args.no_rotate else max(2, int(np.ceil(512e6 / step_bytes)))
     R = min(R, 64)
@@ -122,6 +128,8 @@ def main():
                 d[n] = up(att[n])
         for n in ("target_logits", "drafter_logits", "tokens", "u_accept", "u_final"):
             d[n] = up(ver[n])
+        if args.frontend:
+            d["uncond_logits"] = up(ver_uncond["target_logits"])
         d["out_attn"] = torch.empty((B, H, M, Dh), dtype=torch.float32, device=dev)
         d["vout"] = {"accept_len": torch.empty((B,), dtype=torch.int32, device=dev),
                      "path": torch.empty((B, depth), dtype=torch.int32, device=dev),
@@ -138,10 +146,16 @@ def main():
         lpp.lpp_tree_attention(tree, dtype, d["q"], d["kc"], d["vc"], d["kt"], d["vt"], None,
                                B, H, S, Dh, 0.0, d["out_attn"], attn_ws, stream)
 
-    def verify(d):
-        lpp.lpp_relaxed_verify(tree, d["target_logits"], d["drafter_logits"], cfg.ldv, cfg.vocab_offset, V, B,
-                               d["tokens"], neigh, k, k, cfg.lam, d["u_accept"], d["u_final"], d["vout"],
-                               ver_ws, stream)
+    def verify(d, st=None):
+        st = stream if st is None else st
+        if args.frontend:
+            lpp.lpp_relaxed_verify_sampled(tree, d["target_logits"], d["uncond_logits"], 3.0, 2000, d["drafter_logits"],
+                                           cfg.ldv, cfg.vocab_offset, V, B, d["tokens"], neigh, k, k, cfg.lam,
+                                           d["u_accept"], d["u_final"], d["vout"], ver_ws, st)
+        else:
+            lpp.lpp_relaxed_verify(tree, d["target_logits"], d["drafter_logits"], cfg.ldv, cfg.vocab_offset, V, B,
+                                   d["tokens"], neigh, k, k, cfg.lam, d["u_accept"], d["u_final"], d["vout"],
+                                   ver_ws, st)
 
     def step(i):
         d = reps[i % R]
@@ -169,9 +183,7 @@ def main():
             lpp.lpp_tree_attention(tree, dtype, d["q"], d["kc"], d["vc"], d["kt"], d["vt"], None,
                                    B, H, S, Dh, 0.0, d["out_attn"], attn_ws, global_stream[0])
         def verify_s(d):
-            lpp.lpp_relaxed_verify(tree, d["target_logits"], d["drafter_logits"], cfg.ldv, cfg.vocab_offset, V, B,
-                                   d["tokens"], neigh, k, k, cfg.lam, d["u_accept"], d["u_final"], d["vout"],
-                                   ver_ws, global_stream[0])
+            verify(d, global_stream[0])
         g_all = capture(lambda: [(attention_s(d), verify_s(d)) for d in reps])
         g_one = [capture(lambda d=d: (attention_s(d), verify_s(d))) for d in reps]
         g_attn = capture(lambda: [attention_s(d) for d in reps])
@@ -266,6 +278,7 @@ def main():
            "data": "synthetic",
            "config": {"workload": f"config {cfg.idx} ({cfg.name}): B={B} H={H}x{Dh} S={S} M={M} V={V} k={k} "
                                   f"lambda={cfg.lam}", "replicas_rotated": R, "mean_accept_len": mean_accept,
+                      "frontend": "cfg 3.0 + top-k 2000 fused" if args.frontend else "none (final logits handed in)",
                       "launch": launch},
            "roofline": roofline, "cpu_baseline": cpu, "knn_build": knn}
     print(json.dumps(out))

@@ -174,6 +174,25 @@ int32_t lpp_relaxed_verify_additive(const lpp_tree* tree, const float* target_lo
                                     const float* u_accept, const float* u_final,
                                     const lpp_verify_out* out, void* ws, size_t ws_bytes, void* stream);
 
+/* The same step with the sampling configuration of the paper's experiments in front of the target
+ * softmax (App. B "Models": classifier-free guidance, top-k sampling, temperature 1), fused into the
+ * load of the target rows:
+ *     l(x) = u(x) + cfg_scale * (c(x) - u(x))     c = cond_logits row, u = uncond_logits row
+ *     only the top_k largest l of a row stay (ties with the top_k-th stay too), the rest is -inf
+ *     q = softmax(l)
+ * computed in float32 with the difference, the product and the sum each rounded once, so that which
+ * tokens survive is reproducible.  uncond_logits NULL = no guidance (l = c); top_k 0 or >= V = no
+ * filter.  drafter_logits are taken as they are.  Everything else as in lpp_relaxed_verify (same
+ * workspace query).  Extra errors: LPP_EINVAL for cfg_scale NaN or top_k < 0.
+ */
+int32_t lpp_relaxed_verify_sampled(const lpp_tree* tree, const float* cond_logits,
+                                   const float* uncond_logits, float cfg_scale, int32_t top_k,
+                                   const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                                   int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
+                                   int32_t kstride, int32_t k, float lambda,
+                                   const float* u_accept, const float* u_final,
+                                   const lpp_verify_out* out, void* ws, size_t ws_bytes, void* stream);
+
 /* ---------------------------------------------------------------- commit ---
  * Appends what the step keeps to the KV cache (paper App. A.2: accepted tokens are kept, the rest
  * of the tree is discarded).  For item b the rows r_0 = 0 (the root: the last committed token, not

@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     lpp_build_neighbours, lpp_build_neighbours_workspace,
     lpp_tree_attention, lpp_tree_attention_workspace,
     lpp_relaxed_verify, lpp_relaxed_verify_workspace, lpp_relaxed_verify_additive,
-    lpp_commit_kv,
+    lpp_commit_kv, lpp_relaxed_verify_sampled,
 )

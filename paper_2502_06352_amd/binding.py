@@ -63,6 +63,9 @@ def lib() -> C.CDLL:
                                      C.POINTER(VerifyOut), vp, sz, vp]
     L.lpp_relaxed_verify_additive.restype = i32
     L.lpp_relaxed_verify_additive.argtypes = L.lpp_relaxed_verify.argtypes
+    L.lpp_relaxed_verify_sampled.restype = i32
+    L.lpp_relaxed_verify_sampled.argtypes = [vp, vp, vp, f32, i32, vp, i64, i32, i32, i32, vp, vp, i32, i32, f32, vp, vp,
+                                             C.POINTER(VerifyOut), vp, sz, vp]
     L.lpp_commit_kv.restype = i32
     L.lpp_commit_kv.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
     _lib = L
@@ -162,3 +165,17 @@ def lpp_commit_kv(tree: Tree, dtype: int, k_tree, v_tree, path, accept_len, seq_
     _check(lib().lpp_commit_kv(tree.handle, dtype, _ptr(k_tree), _ptr(v_tree), _ptr(path), _ptr(accept_len),
                                _ptr(seq_len), B, H, S, Dh, _ptr(k_cache), _ptr(v_cache), _ptr(new_len),
                                _stream(stream)), "lpp_commit_kv")
+
+
+def lpp_relaxed_verify_sampled(tree: Tree, cond_logits, uncond_logits, cfg_scale: float, top_k: int,
+                               drafter_logits, ldv: int, vocab_offset: int, V: int, B: int, tokens, neigh,
+                               kstride: int, k: int, lam: float, u_accept, u_final, out: dict, ws,
+                               stream=None) -> None:
+    """As lpp_relaxed_verify, with guidance and top-k applied to the target rows inside the kernel."""
+    vo = VerifyOut(**{n: _ptr(out.get(n)) for n, _ in VerifyOut._fields_})
+    _check(lib().lpp_relaxed_verify_sampled(tree.handle, _ptr(cond_logits), _ptr(uncond_logits), cfg_scale, top_k,
+                                            _ptr(drafter_logits), ldv, vocab_offset, V, B, _ptr(tokens),
+                                            _ptr(neigh), kstride, k, lam, _ptr(u_accept), _ptr(u_final),
+                                            C.byref(vo), _ptr(ws),
+                                            0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
+           "lpp_relaxed_verify_sampled")

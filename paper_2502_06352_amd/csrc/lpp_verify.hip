@@ -54,8 +54,11 @@ struct TreeTab {
 };
 
 struct VerifyArgs {
-  const float* target;
+  const float* target;    // with a sampling front end: the text-conditioned rows
+  const float* uncond;    // null-conditioned rows of the target, or null (no guidance)
   const float* drafter;
+  float cfg_scale;        // guidance scale s: l = u + s (c - u)
+  int32_t top_k;          // keep the top_k largest guided logits of a row (0: keep all)
   int64_t ldv;
   int32_t off, V, M, B, kstride, k, depth;
   int32_t nstage;         // child lists whose first pass is staged in LDS (<= kMaxStage)
@@ -244,7 +247,8 @@ __device__ __forceinline__ float combine_max(const float* s_w, int lane) {
 // the row is therefore a sequence of NCH * NW cells of 256 tokens, cell j * NW + w
 // owned by wave w.  The neighbour list of a child is taken in passes of 2 NT slots,
 // lane `tid` holding slots 2 tid and 2 tid + 1 of the pass.
-template <int NT, int NCH, bool ALIGNED>
+// FRONT: classifier-free guidance and top-k in front of the target softmax (paper App. B "Models").
+template <int NT, int NCH, bool ALIGNED, bool FRONT>
 __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab tt) {
   constexpr int NW = NT / 64;
   constexpr int NC = NCH * NW;             // cells
@@ -265,6 +269,8 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   __shared__ float s_dlog[LPP_MAX_ROWS];
   __shared__ float s_u[LPP_MAX_ROWS];
   __shared__ int s_jstar;
+  __shared__ int s_ncand;
+  __shared__ uint32_t s_tau;
   __shared__ float s_mass;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -283,9 +289,13 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   const int nst = min(nchild, a.nstage);
 
   // ---- every HBM read of the two rows is issued first: nothing else is as long
-  float4 tv[NCH], dv[NCH];
+  float4 tv[NCH], dv[NCH], uv[FRONT ? NCH : 1];
 #pragma unroll
   for (int j = 0; j < NCH; ++j) tv[j] = load_logits4<ALIGNED>(trow, 4 * (tid + NT * j), V);
+  if (FRONT && a.uncond) {
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) uv[FRONT ? j : 0] = load_logits4<ALIGNED>(a.uncond + rowoff, 4 * (tid + NT * j), V);
+  }
   if (nchild > 0) {
 #pragma unroll
     for (int j = 0; j < NCH; ++j) dv[j] = load_logits4<ALIGNED>(drow, 4 * (tid + NT * j), V);
@@ -331,11 +341,185 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   __builtin_amdgcn_sched_barrier(0);   // every load above is issued before anything below waits
   const bool full_row = V == NT * NCH * 4;   // no token of the block's range lies past the vocabulary
 
+  // ---- sampling front end of the target row (App. B "Models": guidance scale, top-k): the
+  // guided logit l = u + s (c - u) in float32, difference, product and sum each rounded once; then
+  // only the top_k largest of the row stay (ties with the k-th stay too), the rest becomes -inf
+  if (FRONT) {
+    const bool guide = a.uncond != nullptr;
+    uint32_t key[NCH][4];       // order-preserving integer image of the guided logits
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      float c[4] = {tv[j].x, tv[j].y, tv[j].z, tv[j].w};
+      const float u[4] = {uv[FRONT ? j : 0].x, uv[FRONT ? j : 0].y, uv[FRONT ? j : 0].z, uv[FRONT ? j : 0].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float l = c[e];
+        if (guide) {
+          const float g = c[e] - u[e];
+          const float sg = a.cfg_scale * g;
+          l = u[e] + sg;
+          if (c[e] == -INFINITY) l = -INFINITY;
+        }
+        if (4 * (tid + NT * j) + e >= V) l = -INFINITY;
+        c[e] = l;
+        const uint32_t b = __float_as_uint(l);
+        key[j][e] = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+      }
+      tv[j] = make_float4(c[0], c[1], c[2], c[3]);
+    }
+    if (a.top_k > 0 && a.top_k < V) {
+      // The top_k-th largest key.  Fast way: 2048 bins spread evenly over the row's range of values
+      // (a monotone map, so whole bins lie above or below the one that holds the answer; spread
+      // values mean few collisions in the LDS histogram), then an exact rank among the few keys of
+      // that bin.  If that bin is crowded (many equal values), a radix select over the key bits
+      // does the same exactly, only slower.  Histograms live in the LDS that r will occupy later.
+      uint32_t* hist = reinterpret_cast<uint32_t*>(smem);          // [2048]
+      uint32_t* cand = hist + 2048;                                // [kCand]
+      constexpr int kCand = 256;
+      uint32_t prefix = 0;
+      bool done = false;
+      {
+        float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < NCH; ++j) {
+          const float c[4] = {tv[j].x, tv[j].y, tv[j].z, tv[j].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (c[e] > -INFINITY && c[e] < INFINITY) { lo = fminf(lo, c[e]); hi = fmaxf(hi, c[e]); }
+        }
+        lo = -wave_max(-lo);
+        hi = wave_max(hi);
+        if (lane == 0) { s_max[0][w] = -lo; s_max[1][w] = hi; }
+        for (int i = tid; i < 2048; i += NT) hist[i] = 0u;
+        if (tid == 0) { s_ncand = 0; s_tau = 0u; }
+        lds_barrier();
+        lo = -combine_max<NW>(s_max[0], lane);
+        hi = combine_max<NW>(s_max[1], lane);
+        const float scale = hi > lo ? 2047.0f / (hi - lo) : 0.f;
+        int bin[NCH][4];
+#pragma unroll
+        for (int j = 0; j < NCH; ++j) {
+          const float c[4] = {tv[j].x, tv[j].y, tv[j].z, tv[j].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float x = (c[e] - lo) * scale;                 // monotone in c; -inf, NaN -> bin 0
+            bin[j][e] = x >= 2047.f ? 2047 : (x >= 0.f ? (int)x : 0);
+            atomicAdd(&hist[bin[j][e]], 1u);
+          }
+        }
+        lds_barrier();
+        int cnt[32];
+        int local = 0;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) { cnt[i] = (int)hist[2047 - 32 * lane - i]; local += cnt[i]; }
+        int incl = local;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int t = __shfl_up(incl, o);
+          if (lane >= o) incl += t;
+        }
+        const unsigned long long bal = __ballot(incl >= a.top_k);
+        const int fl = bal ? __ffsll((long long)bal) - 1 : 63;
+        int bstar = 0, above = 0, inbin = 0;
+        if (lane == fl) {
+          int run = incl - local;
+          bstar = max(2047 - 32 * lane - 31, 0);
+          above = run;
+#pragma unroll
+          for (int i = 0; i < 32; ++i) {
+            if (run + cnt[i] >= a.top_k) { bstar = 2047 - 32 * lane - i; above = run; inbin = cnt[i]; break; }
+            run += cnt[i];
+          }
+        }
+        bstar = __shfl(bstar, fl); above = __shfl(above, fl); inbin = __shfl(inbin, fl);
+        const int need = a.top_k - above;                        // rank inside bin bstar, from the top
+        if (inbin <= kCand) {                                    // uniform
+#pragma unroll
+          for (int j = 0; j < NCH; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (bin[j][e] == bstar) cand[atomicAdd(&s_ncand, 1)] = key[j][e];
+          lds_barrier();
+          const int n = s_ncand;
+          for (int i = tid; i < n; i += NT) {
+            const uint32_t ki = cand[i];
+            int gt = 0, ge = 0;
+            for (int q = 0; q < n; ++q) { gt += cand[q] > ki; ge += cand[q] >= ki; }
+            if (gt < need && need <= ge) s_tau = ki;             // (equal keys write the same value)
+          }
+          lds_barrier();
+          prefix = s_tau;
+          done = true;
+        }
+        lds_barrier();                                           // histogram and list are free again
+      }
+      if (!done) {
+        int need = a.top_k;
+#pragma unroll
+        for (int pass = 0; pass < 3; ++pass) {
+          const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
+          const int bits = pass == 2 ? 10 : 11;
+          const int nb = 1 << bits;
+          for (int i = tid; i < 2048; i += NT) hist[i] = 0u;
+          lds_barrier();
+#pragma unroll
+          for (int j = 0; j < NCH; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const bool in = pass == 0 || (key[j][e] >> (shift + bits)) == (prefix >> (shift + bits));
+              if (in) atomicAdd(&hist[(key[j][e] >> shift) & (nb - 1)], 1u);
+            }
+          lds_barrier();
+          // every wave walks the bins from the top (32 per lane) and finds the one holding the need-th key
+          int cnt[32];
+          int local = 0;
+#pragma unroll
+          for (int i = 0; i < 32; ++i) {
+            const int b = 2047 - 32 * lane - i;
+            cnt[i] = b < nb ? (int)hist[b] : 0;
+            local += cnt[i];
+          }
+          int incl = local;
+#pragma unroll
+          for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+          }
+          const unsigned long long bal = __ballot(incl >= need);
+          const int fl = bal ? __ffsll((long long)bal) - 1 : 63;
+          int found = 0, above = 0;
+          if (lane == fl) {
+            int run = incl - local;
+            found = max(2047 - 32 * lane - 31, 0);
+            above = run;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+              if (run + cnt[i] >= need) { found = 2047 - 32 * lane - i; above = run; break; }
+              run += cnt[i];
+            }
+          }
+          found = __shfl(found, fl);
+          above = __shfl(above, fl);
+          prefix |= (uint32_t)found << shift;
+          need -= above;
+          lds_barrier();            // the histogram is cleared again (or handed over to r) after this
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) {
+        if (key[j][0] < prefix) tv[j].x = -INFINITY;
+        if (key[j][1] < prefix) tv[j].y = -INFINITY;
+        if (key[j][2] < prefix) tv[j].z = -INFINITY;
+        if (key[j][3] < prefix) tv[j].w = -INFINITY;
+      }
+    }
+  }
+
   // ---- softmax statistics of both rows (Sec. 2 notation: q target, p drafter; T = 1)
   float mt = -INFINITY, md = -INFINITY;
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    if (!full_row) tv[j] = mask_logits4(tv[j], 4 * (tid + NT * j), V);
+    if (!full_row && !FRONT) tv[j] = mask_logits4(tv[j], 4 * (tid + NT * j), V);
     if (!full_row || nchild == 0) dv[j] = mask_logits4(dv[j], 4 * (tid + NT * j), nchild > 0 ? V : 0);
     mt = fmaxf(mt, fmaxf(fmaxf(tv[j].x, tv[j].y), fmaxf(tv[j].z, tv[j].w)));
     md = fmaxf(md, fmaxf(fmaxf(dv[j].x, dv[j].y), fmaxf(dv[j].z, dv[j].w)));
@@ -638,11 +822,11 @@ __global__ __launch_bounds__(64) void walk_kernel(VerifyArgs a) {
             a.accept_len + b, a.path + (int64_t)b * a.depth, a.final_token + b);
 }
 
-template <int NT, int NCH, bool ALIGNED>
+template <int NT, int NCH, bool ALIGNED, bool FRONT>
 int32_t launch_rows(const VerifyArgs& a, const TreeTab& tt, hipStream_t stream) {
   static size_t attr_lds = 0;   // largest dynamic LDS size this instantiation was enabled for
   const size_t lds = ((size_t)NT * NCH * 4 + 4) * sizeof(float) + (size_t)a.nstage * NT * sizeof(uint32_t);
-  auto kern = verify_rows_kernel<NT, NCH, ALIGNED>;
+  auto kern = verify_rows_kernel<NT, NCH, ALIGNED, FRONT>;
   if (lds > attr_lds) {
     LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -663,7 +847,8 @@ extern "C" size_t lpp_relaxed_verify_workspace(const lpp_tree* tree, int32_t B, 
 }
 
 namespace {
-int32_t relaxed_verify_impl(int32_t additive, const lpp_tree* tree, const float* target_logits,
+int32_t relaxed_verify_impl(int32_t additive, bool front, const float* uncond_logits, float cfg_scale,
+                            int32_t top_k, const lpp_tree* tree, const float* target_logits,
                             const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
                             int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
                             int32_t kstride, int32_t k, float lambda, const float* u_accept,
@@ -682,7 +867,8 @@ int32_t relaxed_verify_impl(int32_t additive, const lpp_tree* tree, const float*
   if (!tree->d_counters) return LPP_EHIP;
 
   VerifyArgs a;
-  a.target = target_logits; a.drafter = drafter_logits; a.ldv = ldv; a.off = vocab_offset;
+  a.target = target_logits; a.uncond = uncond_logits; a.cfg_scale = cfg_scale; a.top_k = top_k;
+  a.drafter = drafter_logits; a.ldv = ldv; a.off = vocab_offset;
   a.V = V; a.M = tree->M; a.B = B; a.kstride = kstride; a.k = k; a.lambda = lambda; a.additive = additive;
   a.depth = tree->depth > 0 ? tree->depth : 1;
   // Staged lists cost LDS.  When there are several rows per compute unit, two rows resident at
@@ -721,9 +907,11 @@ int32_t relaxed_verify_impl(int32_t additive, const lpp_tree* tree, const float*
   auto aligned16 = [&](const float* p) {
     return p == nullptr || ((reinterpret_cast<uintptr_t>(p + vocab_offset) % 16 == 0) && (ldv % 4 == 0) && (V % 4 == 0));
   };
-  const bool al = aligned16(target_logits) && aligned16(drafter_logits);
+  const bool al = aligned16(target_logits) && aligned16(drafter_logits) && aligned16(uncond_logits);
   int32_t st;
-#define LPP_DISPATCH(T, N) st = al ? launch_rows<T, N, true>(a, tt, s) : launch_rows<T, N, false>(a, tt, s)
+#define LPP_DISPATCH(T, N)                                                                          \
+  st = front ? (al ? launch_rows<T, N, true, true>(a, tt, s) : launch_rows<T, N, false, true>(a, tt, s))  \
+             : (al ? launch_rows<T, N, true, false>(a, tt, s) : launch_rows<T, N, false, false>(a, tt, s))
   if (V <= 2048) LPP_DISPATCH(512, 1);
   else if (V <= 4096) LPP_DISPATCH(512, 2);
   else if (V <= 8192) LPP_DISPATCH(512, 4);
@@ -745,7 +933,7 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
                                       int32_t kstride, int32_t k, float lambda, const float* u_accept,
                                       const float* u_final, const lpp_verify_out* out, void* ws,
                                       size_t ws_bytes, void* stream) {
-  return relaxed_verify_impl(0, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
+  return relaxed_verify_impl(0, false, nullptr, 0.f, 0, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
                              kstride, k, lambda, u_accept, u_final, out, ws, ws_bytes, stream);
 }
 
@@ -756,6 +944,19 @@ extern "C" int32_t lpp_relaxed_verify_additive(const lpp_tree* tree, const float
                                                const float* u_accept, const float* u_final,
                                                const lpp_verify_out* out, void* ws, size_t ws_bytes,
                                                void* stream) {
-  return relaxed_verify_impl(1, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
+  return relaxed_verify_impl(1, false, nullptr, 0.f, 0, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
                              kstride, k, delta, u_accept, u_final, out, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t lpp_relaxed_verify_sampled(const lpp_tree* tree, const float* cond_logits,
+                                              const float* uncond_logits, float cfg_scale, int32_t top_k,
+                                              const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                                              int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
+                                              int32_t kstride, int32_t k, float lambda, const float* u_accept,
+                                              const float* u_final, const lpp_verify_out* out, void* ws,
+                                              size_t ws_bytes, void* stream) {
+  if (cfg_scale != cfg_scale || top_k < 0) return LPP_EINVAL;
+  return relaxed_verify_impl(0, true, uncond_logits, cfg_scale, top_k, tree, cond_logits, drafter_logits, ldv,
+                             vocab_offset, V, B, tokens, neigh, kstride, k, lambda, u_accept, u_final, out, ws,
+                             ws_bytes, stream);
 }
