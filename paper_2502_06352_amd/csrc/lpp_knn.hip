@@ -12,7 +12,7 @@
 //           b* holding the (k-1)-th largest; sweep 2 appends every code whose bin
 //           is >= b* - 1 to the row's candidate list.
 //   rank    per row: exact float64 keys of the candidates (FMA chain in index
-//           order), bitonic sort by (key desc, index asc) in LDS, write the row.
+//           order), rank by (key desc, index asc) with value buckets in LDS, write the row.
 // Why the candidate list is enough: a code that is not a candidate has an
 // approximate similarity below the lower edge e of bin b* - 1, hence an exact key
 // below e + eps, eps bounding the matrix-core rounding.  If the (k-1)-th exact key
@@ -27,6 +27,7 @@
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBins = 1024;
 constexpr float kBinScale = 512.0f;           // bin = floor((s + 1) * 512), clamped
@@ -225,71 +226,203 @@ __device__ __forceinline__ bool before(uint64_t ka, uint32_t ia, uint64_t kb, ui
   return ka > kb || (ka == kb && ia < ib);
 }
 
-// In-LDS bitonic sort of P (power of two) entries by (key desc, idx asc); ends with a barrier.
-__device__ void bitonic_sort(uint64_t* skey, uint32_t* sidx, int P, int tid) {
-  for (int size = 2; size <= P; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int t = tid; t < (P >> 1); t += kRankThreads) {
-        const int lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
-        const int hi = lo | stride;
-        const bool up = (lo & size) == 0;            // this run ends up in "before" order
-        const uint64_t k0 = skey[lo], k1 = skey[hi];
-        const uint32_t i0 = sidx[lo], i1 = sidx[hi];
-        const bool sw = up ? before(k1, i1, k0, i0) : before(k0, i0, k1, i1);
-        if (sw) { skey[lo] = k1; skey[hi] = k0; sidx[lo] = i1; sidx[hi] = i0; }
-      }
-      __syncthreads();
-    }
-  }
+__device__ __forceinline__ double key_value(uint64_t K) {
+  const uint64_t u = (K >> 63) ? (K & 0x7FFFFFFFFFFFFFFFull) : ~K;
+  return __longlong_as_double((long long)u);
 }
 
-__global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a) {
-  extern __shared__ unsigned char smem[];
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+
+// Rank of each of the n entries of (skey, sidx) in the order (key desc, idx asc), without a
+// comparison sort: the keys are spread over NB buckets by a monotone map of their value
+// (bucket 0 = largest), bucket sizes are scanned, the entries' ids are scattered bucket by
+// bucket, and an entry's rank is its bucket's start plus the number of bucket mates that go
+// before it.  The first kk ranks are written to out[1 + rank]; the key of rank kk - 1 is left in
+// *kth.  cur[NB] and ord[n] are LDS scratch.  Ends with a barrier.
+__device__ void bucket_rank(const uint64_t* skey, const uint32_t* sidx, int n, int NB, uint32_t* cur,
+                            uint16_t* ord, uint64_t* s_red, int kk, int32_t* out, uint64_t* kth,
+                            int tid) {
+  const int lane = tid & 63, wv = tid >> 6;
+  uint64_t lo = ~0ull, hi = 0ull;
+  for (int c = tid; c < n; c += kRankThreads) {
+    const uint64_t K = skey[c];
+    lo = K < lo ? K : lo;
+    hi = K > hi ? K : hi;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint64_t l2 = __shfl_xor(lo, o), h2 = __shfl_xor(hi, o);
+    lo = l2 < lo ? l2 : lo;
+    hi = h2 > hi ? h2 : hi;
+  }
+  if (lane == 0) { s_red[2 * wv] = lo; s_red[2 * wv + 1] = hi; }
+  for (int b = tid; b < NB; b += kRankThreads) cur[b] = 0u;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kRankThreads / 64; ++w) {
+    lo = s_red[2 * w] < lo ? s_red[2 * w] : lo;
+    hi = s_red[2 * w + 1] > hi ? s_red[2 * w + 1] : hi;
+  }
+  const double xlo = key_value(lo), xhi = key_value(hi);
+  const double span = xhi - xlo;
+  // span may be 0, inf or NaN (equal, infinite or NaN keys): then everything shares bucket 0
+  const double scale = (span > 0.0 && span < 1.0e300) ? (double)NB / span : 0.0;
+  auto bucket_of = [&](uint64_t K) -> int {
+    const double f = (xhi - key_value(K)) * scale;        // monotone non-increasing in K
+    int b = f >= (double)(NB - 1) ? NB - 1 : (int)f;
+    return f > 0.0 ? b : 0;                                // NaN and negatives to bucket 0
+  };
+  for (int c = tid; c < n; c += kRankThreads) atomicAdd(&cur[bucket_of(skey[c])], 1u);
+  __syncthreads();
+  // exclusive scan of the NB counts: each lane owns NB / kRankThreads consecutive buckets
+  {
+    const int per = NB / kRankThreads;                     // NB is a multiple of kRankThreads
+    uint32_t local = 0u;
+    for (int j = 0; j < per; ++j) local += cur[tid * per + j];
+    uint32_t incl = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t t = __shfl_up(incl, o);
+      if (lane >= o) incl += t;
+    }
+    uint32_t* s_wt = reinterpret_cast<uint32_t*>(s_red + 8);
+    if (lane == 63) s_wt[wv] = incl;
+    __syncthreads();
+    uint32_t run = incl - local;
+    for (int w = 0; w < wv; ++w) run += s_wt[w];
+    for (int j = 0; j < per; ++j) {
+      const uint32_t cnt = cur[tid * per + j];
+      cur[tid * per + j] = run;
+      run += cnt;
+    }
+  }
+  __syncthreads();
+  for (int c = tid; c < n; c += kRankThreads) {
+    const uint32_t pos = atomicAdd(&cur[bucket_of(skey[c])], 1u);
+    ord[pos] = (uint16_t)c;
+  }
+  __syncthreads();
+  // cur[b] is now the end of bucket b; its start is the end of bucket b - 1
+  for (int c = tid; c < n; c += kRankThreads) {
+    const uint64_t K = skey[c];
+    const uint32_t I = sidx[c];
+    const int b = bucket_of(K);
+    const int beg = b ? (int)cur[b - 1] : 0, end = (int)cur[b];
+    int rank = beg;
+    for (int m = beg; m < end; ++m) {
+      const int o = ord[m];
+      rank += before(skey[o], sidx[o], K, I) ? 1 : 0;
+    }
+    if (rank == kk - 1) *kth = K;
+    if (rank < kk) out[1 + rank] = (int32_t)I;
+  }
+  __syncthreads();
+}
+
+// CH floats of a codebook row are staged per step: a wave loads 64 candidate rows with 16-byte
+// pieces (whole 64- or 128-byte segments per row), parks them in its own LDS tile and every lane
+// then runs the float64 chain of its own candidate over the tile row.
+template <int CH>
+__global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P) {
+  constexpr int LPR = CH / 4;            // lanes per staged row piece
+  constexpr int RPI = 64 / LPR;          // rows per load instruction
+  constexpr int PITCH = CH + 4;          // floats; 16-byte reads of 16 consecutive rows hit distinct banks
+  extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_hist[256];
   __shared__ int s_misc[8];
+  __shared__ uint64_t s_red[12];
+  __shared__ uint64_t s_kth;
   const int tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
   const int i = blockIdx.x;
   const int V = a.V, D = a.D, DP = a.DP, kk = a.k - 1;
   int32_t* out = a.neigh + (int64_t)i * a.k;
-  if (kk == 0) {
-    if (tid == 0) out[0] = i;
-    return;
-  }
-  // P = power of two >= cap (set by the host through the dynamic LDS size)
-  int P = 1;
-  while (P < a.cap) P <<= 1;
+  if (tid == 0) out[0] = i;
+  if (kk == 0) return;
   uint64_t* skey = reinterpret_cast<uint64_t*>(smem);
   uint32_t* sidx = reinterpret_cast<uint32_t*>(skey + P);
-  float* ei = reinterpret_cast<float*>(sidx + P);
-  for (int d = tid; d < DP; d += kRankThreads) ei[d] = a.Ep[(int64_t)i * DP + d];
+  double* eid = reinterpret_cast<double*>(sidx + P);     // the query row as doubles
+  float* ei = reinterpret_cast<float*>(eid + DP);         // and as loaded (exact path)
+  // scratch: staging tiles while keys are computed, then the buckets of the ranking
+  unsigned char* scratch = reinterpret_cast<unsigned char*>(ei + DP);
+  float* tile = reinterpret_cast<float*>(scratch) + wv * 64 * PITCH;
+  uint32_t* cur = reinterpret_cast<uint32_t*>(scratch);
+  uint16_t* ord = reinterpret_cast<uint16_t*>(cur + P);
+  for (int d = tid; d < DP; d += kRankThreads) {
+    const float v = a.Ep[(int64_t)i * DP + d];
+    ei[d] = v;
+    eid[d] = (double)v;
+  }
   __syncthreads();
 
   const int n = a.cnt[i];
   bool slow = n > a.cap || n < kk;          // list overflowed: only the exact path is safe
   if (!slow) {
-    for (int c = tid; c < P; c += kRankThreads) {
-      if (c < n) {
-        const int j = a.cand[(int64_t)i * a.cap + c];
-        skey[c] = exact_key(ei, a.Ep, DP, D, j);
-        sidx[c] = (uint32_t)j;
-      } else {
-        skey[c] = 0ull;
-        sidx[c] = 0xFFFFFFFFu;
+    const uint16_t* crow = a.cand + (int64_t)i * a.cap;
+    const int nsteps = (D + CH - 1) / CH;
+    for (int base = wv * 64; base < n; base += kRankThreads) {
+      const int c = base + lane;
+      const int jown = c < n ? (int)crow[c] : i;
+      double acc = 0.0;
+      f32x4 piece[LPR];
+#pragma unroll
+      for (int q = 0; q < LPR; ++q) {
+        const int jr = __shfl(jown, q * RPI + lane / LPR);
+        piece[q] = *reinterpret_cast<const f32x4*>(a.Ep + (int64_t)jr * DP + (lane % LPR) * 4);
       }
+      for (int st = 0; st < nsteps; ++st) {
+#pragma unroll
+        for (int q = 0; q < LPR; ++q)
+          *reinterpret_cast<f32x4*>(tile + (q * RPI + lane / LPR) * PITCH + (lane % LPR) * 4) = piece[q];
+        wave_lds_sync();
+        if (st + 1 < nsteps) {
+#pragma unroll
+          for (int q = 0; q < LPR; ++q) {
+            const int jr = __shfl(jown, q * RPI + lane / LPR);
+            piece[q] = *reinterpret_cast<const f32x4*>(a.Ep + (int64_t)jr * DP + (st + 1) * CH + (lane % LPR) * 4);
+          }
+        }
+        const double* eq = eid + st * CH;
+        if (D - st * CH >= CH) {
+#pragma unroll
+          for (int t0 = 0; t0 < CH; t0 += 4) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(tile + lane * PITCH + t0);
+            const f64x2 e0 = *reinterpret_cast<const f64x2*>(eq + t0);
+            const f64x2 e1 = *reinterpret_cast<const f64x2*>(eq + t0 + 2);
+            acc = __builtin_fma(e0[0], (double)v[0], acc);
+            acc = __builtin_fma(e0[1], (double)v[1], acc);
+            acc = __builtin_fma(e1[0], (double)v[2], acc);
+            acc = __builtin_fma(e1[1], (double)v[3], acc);
+          }
+        } else {
+          const int lim = D - st * CH;                       // > 0: the ragged last step
+          for (int t = 0; t < lim; ++t) acc = __builtin_fma(eq[t], (double)tile[lane * PITCH + t], acc);
+        }
+        wave_lds_sync();
+      }
+      if (c < n) { skey[c] = orderable(acc); sidx[c] = (uint32_t)jown; }
     }
     __syncthreads();
-    bitonic_sort(skey, sidx, P, tid);
+    bucket_rank(skey, sidx, n, P, cur, ord, s_red, kk, out, &s_kth, tid);
     // can a code outside the candidate list still belong to the row?
     const int bs = a.bstar[i];
     if (bs - 1 >= 1) {
       const float edge = (float)(bs - 1) / kBinScale - 1.0f;      // lower edge of bin b* - 1
       const float eps = (float)(DP + 4) * 1.1920929e-07f * a.norms[i] * __uint_as_float(*a.maxnorm) * 1.001f + 1e-37f;
-      slow = skey[kk - 1] < orderable((double)edge + (double)eps);
+      slow = s_kth < orderable((double)edge + (double)eps);
     }
+    if (!slow) return;
+    // the row was written from the candidate list and is written again below by other lanes:
+    // make the first version reach memory before any lane goes on (rare path)
+    __threadfence();
     __syncthreads();
   }
-  if (slow) {
-    // ---- exact path over all V codes: radix select of the kk-th largest key
+  // ---- exact path over all V codes: radix select of the kk-th largest key
+  {
     uint64_t prefix = 0ull;
     int need = kk;
     for (int byte = 7; byte >= 0; --byte) {
@@ -320,9 +453,7 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a) {
     // lowest-index codes equal to it
     const int n_gt = kk - need;
     if (tid == 0) { s_misc[2] = 0; s_misc[3] = 0; }
-    for (int c = tid; c < P; c += kRankThreads) { skey[c] = 0ull; sidx[c] = 0xFFFFFFFFu; }
     __syncthreads();
-    const int lane = tid & 63, wv = tid >> 6;
     for (int j0 = 0; j0 < V; j0 += kRankThreads) {
       const int j = j0 + tid;
       uint64_t K = 0ull;
@@ -348,10 +479,8 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a) {
       if (tid == 0) s_misc[3] += s_hist[0] + s_hist[1] + s_hist[2] + s_hist[3];
       __syncthreads();
     }
-    bitonic_sort(skey, sidx, P, tid);
+    bucket_rank(skey, sidx, kk, P, cur, ord, s_red, kk, out, &s_kth, tid);
   }
-  if (tid == 0) out[0] = i;
-  for (int c = tid; c < kk; c += kRankThreads) out[1 + c] = (int32_t)sidx[c];
 }
 
 int32_t cap_for(int32_t k) { return (int32_t)lpp_align_up((size_t)(k - 1) + kSlack, 64); }
@@ -437,16 +566,25 @@ extern "C" int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, in
     }
     if (st != LPP_OK) return st;
   }
-  static bool attr_set = false;
-  int P = 1;
+  int P = kRankThreads;
   while (P < L.cap) P <<= 1;
-  const size_t lds = (size_t)P * 12 + (size_t)L.DP * sizeof(float);
-  if (!attr_set) {
-    LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(knn_rank_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-    attr_set = true;
+  const int CH = L.DP < 32 ? 16 : 32;
+  // keys + indices + the query row (as doubles and floats) + max(staging tiles, bucket counters and order)
+  const size_t stage = (size_t)(kRankThreads / 64) * 64 * (CH + 4) * sizeof(float);
+  const size_t sortb = (size_t)P * 6;
+  const size_t lds = (size_t)P * 12 + (size_t)L.DP * 12 + (stage > sortb ? stage : sortb);
+  if (lds > 150 * 1024) return LPP_EUNSUPPORTED;
+  static size_t attr_lds[2] = {0, 0};
+  const void* fn = CH == 16 ? reinterpret_cast<const void*>(knn_rank_kernel<16>)
+                            : reinterpret_cast<const void*>(knn_rank_kernel<32>);
+  if (lds > attr_lds[CH == 32]) {
+    LPP_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_lds[CH == 32] = lds;
   }
-  hipLaunchKernelGGL(knn_rank_kernel, dim3((unsigned)V), dim3(kRankThreads), lds, s, a);
+  if (CH == 16)
+    hipLaunchKernelGGL(knn_rank_kernel<16>, dim3((unsigned)V), dim3(kRankThreads), lds, s, a, P);
+  else
+    hipLaunchKernelGGL(knn_rank_kernel<32>, dim3((unsigned)V), dim3(kRankThreads), lds, s, a, P);
   LPP_HIP_TRY(hipGetLastError());
   return LPP_OK;
 }
