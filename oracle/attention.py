@@ -28,23 +28,29 @@ def tree_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
                    k_tree: np.ndarray, v_tree: np.ndarray, parent: np.ndarray,
                    seq_len: Optional[np.ndarray] = None,
                    scale: Optional[float] = None) -> np.ndarray:
-    """q,k_tree,v_tree [B,H,M,Dh]; k_cache,v_cache [B,H,S,Dh] -> out [B,H,M,Dh] (float64).
+    """q [B,H,M,Dh]; k_tree,v_tree [B,Hkv,M,Dh]; k_cache,v_cache [B,Hkv,S,Dh] -> out [B,H,M,Dh] (float64).
 
     ``seq_len[b]`` (default S) = number of valid cached positions of item b.
+    ``Hkv`` divides ``H``: query head h reads key/value head h // (H // Hkv) (grouped-query
+    attention; Hkv == H is the plain multi-head case the paper's models use).
     """
     q = np.asarray(q, dtype=np.float64)
     B, H, M, Dh = q.shape
     S = k_cache.shape[2]
+    Hkv = k_tree.shape[1]
+    assert H % Hkv == 0 and k_cache.shape[1] == Hkv and v_cache.shape[1] == Hkv and v_tree.shape[1] == Hkv
+    group = H // Hkv
     scale = 1.0 / np.sqrt(Dh) if not scale else float(scale)
     vis = ancestor_mask(parent)
     out = np.zeros((B, H, M, Dh), dtype=np.float64)
     for b in range(B):
         Sb = S if seq_len is None else int(seq_len[b])
         for h in range(H):
-            K = np.concatenate([np.asarray(k_cache[b, h, :Sb], dtype=np.float64),
-                                np.asarray(k_tree[b, h], dtype=np.float64)], axis=0)
-            Vv = np.concatenate([np.asarray(v_cache[b, h, :Sb], dtype=np.float64),
-                                 np.asarray(v_tree[b, h], dtype=np.float64)], axis=0)
+            g = h // group
+            K = np.concatenate([np.asarray(k_cache[b, g, :Sb], dtype=np.float64),
+                                np.asarray(k_tree[b, g], dtype=np.float64)], axis=0)
+            Vv = np.concatenate([np.asarray(v_cache[b, g, :Sb], dtype=np.float64),
+                                 np.asarray(v_tree[b, g], dtype=np.float64)], axis=0)
             s = (q[b, h] @ K.T) * scale                      # [M, Sb+M]
             s[:, Sb:][~vis] = -np.inf
             s = s - s.max(axis=1, keepdims=True)

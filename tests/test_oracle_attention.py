@@ -96,3 +96,34 @@ def test_constant_values_and_seq_len():
     vis = ancestor_mask(parent)
     for i in range(M):
         assert np.array_equal(c[:, :, i], d[:, :, i]) == (not vis[i, 2])
+
+
+def test_grouped_query_heads_equal_repeated_key_value_heads_and_library():
+    """Grouped-query attention: query head h reads key/value head h // (H // Hkv).  Repeating every
+    key/value head H // Hkv times must give plain multi-head attention (checked against the pinned
+    multi-head path and against the library routine on the repeated tensors); a head permutation
+    that breaks the grouping must change the result."""
+    rng = np.random.default_rng(11)
+    parent = static_tree((3, 3, 2), 10)
+    B, H, Hkv, M, Dh, S = 2, 6, 2, len(parent), 8, 7
+    q = rng.standard_normal((B, H, M, Dh))
+    kc, vc = rng.standard_normal((2, B, Hkv, S, Dh))
+    kt, vt = rng.standard_normal((2, B, Hkv, M, Dh))
+    seq_len = np.array([7, 4])
+    out = tree_attention(q, kc, vc, kt, vt, parent, seq_len=seq_len)
+    rep = lambda x: np.repeat(x, H // Hkv, axis=1)
+    want = tree_attention(q, rep(kc), rep(vc), rep(kt), rep(vt), parent, seq_len=seq_len)
+    assert np.array_equal(out, want)
+    for b in range(B):
+        Sb = int(seq_len[b])
+        mask = np.concatenate([np.ones((M, Sb), dtype=bool), ancestor_mask(parent)], axis=1)
+        K = np.concatenate([rep(kc)[b:b + 1, :, :Sb], rep(kt)[b:b + 1]], axis=2)
+        Vv = np.concatenate([rep(vc)[b:b + 1, :, :Sb], rep(vt)[b:b + 1]], axis=2)
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(q[b:b + 1]), torch.from_numpy(K), torch.from_numpy(Vv),
+            attn_mask=torch.from_numpy(mask))
+        assert np.abs(out[b:b + 1] - ref.numpy()).max() < 1e-12
+    # interleaved assignment (h % Hkv) is a different function
+    til = lambda x: np.tile(x, (1, H // Hkv, 1, 1))
+    other = tree_attention(q, til(kc), til(vc), til(kt), til(vt), parent, seq_len=seq_len)
+    assert np.abs(other - out).max() > 1e-3
