@@ -47,6 +47,12 @@ def main():
     ap.add_argument("--frontend", action="store_true",
                     help="verify through lpp_relaxed_verify_sampled (guidance 3.0 + top-k 2000 fused; reads one more "
                          "target row set); not the headline configuration")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="attention launches per step, each on its own K/V cache (a target's layer count); "
+                         "the headline step has one")
+    ap.add_argument("--kv-heads", type=int, default=0,
+                    help="key/value heads shared by groups of query heads (lpp_tree_attention_gqa); 0 = multi-head")
+    ap.add_argument("--out-bf16", action="store_true", help="bf16 attention output (lpp_tree_attention_gqa)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three device copies of 256 MiB (a known size to scale rocprofv3 byte counters by)")
     args = ap.parse_args()
@@ -79,6 +85,19 @@ def main():
     # ---- inputs (CPU, seeded) -> HBM
     E = make_codebook(cfg)
     att = make_attention_inputs(cfg)
+    Hkv = args.kv_heads if args.kv_heads > 0 else H
+    L = max(1, args.layers)
+    gqa_call = Hkv != H or args.out_bf16
+    if H % Hkv != 0:
+        print("bench.py: --kv-heads must divide the head count %d" % H, file=sys.stderr)
+        sys.exit(2)
+    if Hkv != H:
+        import dataclasses
+        kv = make_attention_inputs(dataclasses.replace(cfg, H=Hkv), salt=1)
+        for n in ("kc", "vc", "kt", "vt"):
+            att[n] = kv[n]
+            if n + "_bits" in kv:
+                att[n + "_bits"] = kv[n + "_bits"]
     ver = make_verify_inputs(cfg, parent, rho=0.8)
     ver_uncond = make_verify_inputs(cfg, parent, rho=0.0, salt=100) if args.frontend else None
 
@@ -112,9 +131,13 @@ def main():
         del src, dst
 
     attn_bytes, verify_bytes = algorithmic_bytes(cfg, n_parents)
+    if gqa_call:
+        e = 2 if cfg.kv_dtype == "bf16" else 4
+        attn_bytes = (2 * B * Hkv * S * Dh * e + B * (H + 2 * Hkv) * M * Dh * e
+                      + (2 if args.out_bf16 else 4) * B * H * M * Dh)
     if args.frontend:
         verify_bytes += 4 * B * V * M            # the null-conditioned target rows
-    step_bytes = attn_bytes + verify_bytes
+    step_bytes = L * attn_bytes + verify_bytes
     R = 1 if args.no_rotate else max(2, int(np.ceil(512e6 / step_bytes)))
     R = min(R, 64)
     reps = []
@@ -130,7 +153,10 @@ def main():
             d[n] = up(ver[n])
         if args.frontend:
             d["uncond_logits"] = up(ver_uncond["target_logits"])
-        d["out_attn"] = torch.empty((B, H, M, Dh), dtype=torch.float32, device=dev)
+        # further layers: device copies of the first layer's tensors (distinct addresses, same values)
+        d["layers"] = [{n: (d[n] if l == 0 else d[n].clone()) for n in ("q", "kc", "vc", "kt", "vt")} for l in range(L)]
+        d["out_attn"] = torch.empty((B, H, M, Dh), dtype=torch.bfloat16 if args.out_bf16 else torch.float32,
+                                    device=dev)
         d["vout"] = {"accept_len": torch.empty((B,), dtype=torch.int32, device=dev),
                      "path": torch.empty((B, depth), dtype=torch.int32, device=dev),
                      "final_token": torch.empty((B,), dtype=torch.int32, device=dev),
@@ -142,9 +168,16 @@ def main():
     dtype = lpp.LPP_BF16 if cfg.kv_dtype == "bf16" else lpp.LPP_F32
     stream = torch.cuda.current_stream()
 
-    def attention(d):
-        lpp.lpp_tree_attention(tree, dtype, d["q"], d["kc"], d["vc"], d["kt"], d["vt"], None,
-                               B, H, S, Dh, 0.0, d["out_attn"], attn_ws, stream)
+    def attention(d, st=None):
+        st = stream if st is None else st
+        for x in d["layers"]:
+            if gqa_call:
+                lpp.lpp_tree_attention_gqa(tree, dtype, lpp.LPP_BF16 if args.out_bf16 else lpp.LPP_F32, x["q"], x["kc"],
+                                           x["vc"], x["kt"], x["vt"], None, B, H, Hkv, S, Dh, 0.0, d["out_attn"],
+                                           attn_ws, st)
+            else:
+                lpp.lpp_tree_attention(tree, dtype, x["q"], x["kc"], x["vc"], x["kt"], x["vt"], None,
+                                       B, H, S, Dh, 0.0, d["out_attn"], attn_ws, st)
 
     def verify(d, st=None):
         st = stream if st is None else st
@@ -180,8 +213,7 @@ def main():
             return g
         global_stream = [stream]
         def attention_s(d):
-            lpp.lpp_tree_attention(tree, dtype, d["q"], d["kc"], d["vc"], d["kt"], d["vt"], None,
-                                   B, H, S, Dh, 0.0, d["out_attn"], attn_ws, global_stream[0])
+            attention(d, global_stream[0])
         def verify_s(d):
             verify(d, global_stream[0])
         g_all = capture(lambda: [(attention_s(d), verify_s(d)) for d in reps])
@@ -236,7 +268,7 @@ def main():
         torch.cuda.synchronize()
         return ev[0].elapsed_time(ev[1]) / n
 
-    attn_ms = device_ms("a")
+    attn_ms = device_ms("a") / L             # per launch (one layer)
     verify_ms = device_ms("v")
     kern = {"tree_attention": {"ms": attn_ms, "bytes": attn_bytes, "GBs": attn_bytes / attn_ms / 1e6},
             "relaxed_verify": {"ms": verify_ms, "bytes": verify_bytes, "GBs": verify_bytes / verify_ms / 1e6}}
@@ -254,7 +286,7 @@ def main():
 
     # ---- CPU baseline: the float64 numpy oracle, as it stands, on this host
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and L == 1:      # (the oracle's step has one attention layer)
         from oracle import relaxed_verify, tree_attention
         neigh_h = neigh.cpu().numpy()           # input table for the oracle's verify step
         nb = min(B, 1 if cfg.idx >= 5 else B)
@@ -279,6 +311,8 @@ def main():
            "config": {"workload": f"config {cfg.idx} ({cfg.name}): B={B} H={H}x{Dh} S={S} M={M} V={V} k={k} "
                                   f"lambda={cfg.lam}", "replicas_rotated": R, "mean_accept_len": mean_accept,
                       "frontend": "cfg 3.0 + top-k 2000 fused" if args.frontend else "none (final logits handed in)",
+                      "attention_layers_per_step": L, "kv_heads": Hkv,
+                      "attention_out": "bf16" if args.out_bf16 else "f32",
                       "launch": launch},
            "roofline": roofline, "cpu_baseline": cpu, "knn_build": knn}
     print(json.dumps(out))

@@ -112,6 +112,24 @@ int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype,
                            int32_t B, int32_t H, int32_t S, int32_t Dh, float scale,
                            float* out, void* ws, size_t ws_bytes, void* stream);
 
+/* The same attention (Sec. 2.1; App. A.2) for targets whose key/value heads are shared by
+ * groups of query heads, and with a choice of output type:
+ *   Hkv       key/value heads; must divide H; query head h reads key/value head
+ *             h / (H / Hkv)  (Hkv == H is the call above)
+ *   k_tree, v_tree   [device] [B, Hkv, M, Dh];  k_cache, v_cache  [device] [B, Hkv, S, Dh]
+ *   out_dtype LPP_F32 or LPP_BF16: element type of out [B, H, M, Dh]; bf16 is rounded to
+ *             nearest even from the float32 result
+ * Everything else, the workspace query (by H) included, is as for lpp_tree_attention.  The
+ * query heads of one key/value head run next to each other on one XCD, so that the shared
+ * keys and values leave HBM once.  Errors: as above, plus LPP_EINVAL when Hkv < 1, Hkv > H
+ * or H % Hkv != 0, and LPP_EUNSUPPORTED for an unknown out_dtype.
+ */
+int32_t lpp_tree_attention_gqa(const lpp_tree* tree, int32_t dtype, int32_t out_dtype,
+                               const void* q, const void* k_cache, const void* v_cache,
+                               const void* k_tree, const void* v_tree, const int32_t* seq_len,
+                               int32_t B, int32_t H, int32_t Hkv, int32_t S, int32_t Dh, float scale,
+                               void* out, void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------- relaxed verify ---
  * Softmax of every row, relaxed acceptance of every drafted node and the walk
  * down the tree (paper Sec. 4; Sec. 2.2; App. A.2 Eq. 1-2).  For row P with

@@ -7,7 +7,7 @@ from .binding import (  # noqa: F401
     LIB_PATH, LPP_BF16, LPP_F32, LPP_OK, LPP_EINVAL, LPP_EUNSUPPORTED, LPP_ENOWORKSPACE, LPP_EHIP,
     LppError, Tree, lib,
     lpp_build_neighbours, lpp_build_neighbours_workspace,
-    lpp_tree_attention, lpp_tree_attention_workspace,
+    lpp_tree_attention, lpp_tree_attention_gqa, lpp_tree_attention_workspace,
     lpp_relaxed_verify, lpp_relaxed_verify_workspace, lpp_relaxed_verify_additive,
     lpp_commit_kv, lpp_relaxed_verify_sampled,
 )

@@ -56,6 +56,8 @@ def lib() -> C.CDLL:
     L.lpp_tree_attention_workspace.argtypes = [vp, i32, i32, i32, i32]
     L.lpp_tree_attention.restype = i32
     L.lpp_tree_attention.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, vp, sz, vp]
+    L.lpp_tree_attention_gqa.restype = i32
+    L.lpp_tree_attention_gqa.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, sz, vp]
     L.lpp_relaxed_verify_workspace.restype = sz
     L.lpp_relaxed_verify_workspace.argtypes = [vp, i32, i32, i32]
     L.lpp_relaxed_verify.restype = i32
@@ -130,6 +132,14 @@ def lpp_tree_attention(tree: Tree, dtype: int, q, k_cache, v_cache, k_tree, v_tr
                                     _ptr(v_tree), _ptr(seq_len), B, H, S, Dh, scale, _ptr(out), _ptr(ws),
                                     0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
            "lpp_tree_attention")
+
+
+def lpp_tree_attention_gqa(tree: Tree, dtype: int, out_dtype: int, q, k_cache, v_cache, k_tree, v_tree, seq_len,
+                           B: int, H: int, Hkv: int, S: int, Dh: int, scale: float, out, ws, stream=None) -> None:
+    _check(lib().lpp_tree_attention_gqa(tree.handle, dtype, out_dtype, _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                        _ptr(k_tree), _ptr(v_tree), _ptr(seq_len), B, H, Hkv, S, Dh, scale,
+                                        _ptr(out), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                        _stream(stream)), "lpp_tree_attention_gqa")
 
 
 def lpp_relaxed_verify_workspace(tree: Tree, B: int, V: int, k: int) -> int:

@@ -60,10 +60,12 @@ struct AttnArgs {
   const int32_t* seq_len;
   const uint64_t* anc;
   int32_t B, H, S, M, words;
+  int32_t Hkv, gq;                   // key/value heads and query heads per key/value head (H = Hkv * gq)
+  int32_t out_bf16;                  // out holds bf16 instead of float
   int32_t nsplit, msplits, mtiles;   // mtiles = ceil(M / 16)
-  uint32_t rc_perbh, rc_msplits, rc_H, rc_nsplit;   // ceil(2^32 / d): n / d = mulhi(n, rc) while n d < 2^32
+  uint32_t rc_perbh, rc_msplits, rc_H, rc_nsplit, rc_gq;   // ceil(2^32 / d): n / d = mulhi(n, rc) while n d < 2^32
   float scale_log2;                  // scale * log2(e)
-  float* out;                        // [B,H,M,Dh]
+  float* out;                        // [B,H,M,Dh] float, or bf16 when out_bf16
   float* ws_o;                       // [BH][nsplit][mtiles*16][Dh]   unnormalised partial O
   float* ws_ml;                      // [BH][nsplit][mtiles*16][2]    (reference max in log2 units, sum)
   int32_t* counters;                 // [BH * msplits] zero between calls, or null: separate merge kernel
@@ -88,6 +90,14 @@ __device__ __forceinline__ void wave_lds_sync() {
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round to nearest even (hardware convert)
   const bf16x2 v = {(__bf16)lo, (__bf16)hi};
   return __builtin_bit_cast(uint32_t, v);
+}
+
+// four consecutive output elements starting at element index e of the output tensor
+__device__ __forceinline__ void store_out4(float* out, bool as_bf16, int64_t e, float4 v) {
+  if (as_bf16)
+    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + e) = make_uint2(pack_bf16(v.x, v.y), pack_bf16(v.z, v.w));
+  else
+    *reinterpret_cast<float4*>(out + e) = v;
 }
 
 // One key group in flight: K as the A operand of S^T = K Q^T, V as loaded (row-major chunks).
@@ -124,15 +134,18 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   const int kw = wave % KW, rw = wave / KW;
   LPP_ATS(0);
 
-  // block -> (batch*head, key split, row split); all blocks of one head share an XCD
+  // block -> (batch*head, key split, row split); all blocks of one key/value head (every row range
+  // and every query head that reads it) share an XCD and follow each other in launch order
   const uint32_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const uint32_t per_bh = (uint32_t)(a.nsplit * a.msplits);
   const uint32_t hq = div_rc(slot, per_bh, a.rc_perbh), hr = slot - hq * per_bh;
-  const int BH = a.B * a.H;
+  const uint32_t kvq = div_rc(hq, (uint32_t)a.gq, a.rc_gq), qg = hq - kvq * (uint32_t)a.gq;
+  const int KVBH = a.B * a.Hkv;
   // (no early exit for the padding blocks of the last XCD round: a branch here would keep every
   // later argument load behind it; they redo the last head's work and write nothing)
-  const bool live = (int)(hq * 8 + xcd) < BH;
-  const int bh = min((int)(hq * 8 + xcd), BH - 1);
+  const bool live = (int)(kvq * 8 + xcd) < KVBH;
+  const int kvbh = min((int)(kvq * 8 + xcd), KVBH - 1);     // batch * Hkv + key/value head
+  const int bh = kvbh * a.gq + (int)qg;                     // batch * H + query head
   const int split = (int)div_rc(hr, (uint32_t)a.msplits, a.rc_msplits), ms = (int)hr - split * a.msplits;
   const int b = (int)div_rc((uint32_t)bh, (uint32_t)a.H, a.rc_H);
   const int M = a.M, S = a.S;
@@ -142,10 +155,10 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   const int GC = (seq + 31) >> 5, GT = (M + 31) >> 5, G = GC + GT;
   const int gbeg = (int)div_rc((uint32_t)(split * G), (uint32_t)a.nsplit, a.rc_nsplit);
   const int gend = (int)div_rc((uint32_t)((split + 1) * G), (uint32_t)a.nsplit, a.rc_nsplit);
-  const uint16_t* kc = a.kc + (int64_t)bh * S * DH;
-  const uint16_t* vc = a.vc + (int64_t)bh * S * DH;
-  const uint16_t* kt = a.kt + (int64_t)bh * M * DH;
-  const uint16_t* vt = a.vt + (int64_t)bh * M * DH;
+  const uint16_t* kc = a.kc + (int64_t)kvbh * S * DH;
+  const uint16_t* vc = a.vc + (int64_t)kvbh * S * DH;
+  const uint16_t* kt = a.kt + (int64_t)kvbh * M * DH;
+  const uint16_t* vt = a.vt + (int64_t)kvbh * M * DH;
 
   // Key groups [0, GF) lie wholly inside the cache: no mask, no bounds.  The others (the ragged
   // end of the cache and the tree keys) go through the general path after them.
@@ -460,7 +473,7 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
     if (a.nsplit == 1) {
       const float inv = 1.0f / bl;
       v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
-      *reinterpret_cast<float4*>(a.out + ((int64_t)bh * M + m) * DH + c4 * 4) = v;
+      store_out4(a.out, a.out_bf16 != 0, ((int64_t)bh * M + m) * DH + c4 * 4, v);
     } else {
       const int64_t prow = ((int64_t)bh * a.nsplit + split) * rows_pad + m;
       float* dst = a.ws_o + prow * DH + c4 * 4;
@@ -515,8 +528,8 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
       acc.w += f * __hip_atomic_load(src + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     const float inv = 1.0f / ll;
-    *reinterpret_cast<float4*>(a.out + ((int64_t)bh * M + m) * DH + c4 * 4) =
-        make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+    store_out4(a.out, a.out_bf16 != 0, ((int64_t)bh * M + m) * DH + c4 * 4,
+               make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv));
   }
   LPP_ATS(6);
   if (threadIdx.x == 0)   // ready for the next call
@@ -547,8 +560,8 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnArgs a) {
     acc.x += f * v.x; acc.y += f * v.y; acc.z += f * v.z; acc.w += f * v.w;
   }
   const float inv = 1.0f / ll;
-  *reinterpret_cast<float4*>(a.out + row * DH + c4 * 4) =
-      make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+  store_out4(a.out, a.out_bf16 != 0, row * DH + c4 * 4,
+             make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv));
 }
 
 // ---------------------------------------------------------------- fp32 path
@@ -557,6 +570,7 @@ struct AttnArgsF32 {
   const float* q; const float* kc; const float* vc; const float* kt; const float* vt;
   const int32_t* seq_len; const uint64_t* anc;
   int32_t B, H, S, M, words, Dh;
+  int32_t gq, out_bf16;     // query heads per key/value head; out holds bf16 instead of float
   float scale;
   float* out;
 };
@@ -571,6 +585,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
   __shared__ float s_acc[4][128];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = blockIdx.x, bh = blockIdx.y, b = bh / a.H;
+  const int kvbh = bh / a.gq;            // batch * Hkv + key/value head (H = Hkv * gq)
   const int Dh = a.Dh, M = a.M, S = a.S;
   int seq = S;
   if (a.seq_len) seq = min(max(a.seq_len[b], 0), S);     // (everything below depends on it anyway)
@@ -584,7 +599,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
     const int t = j - seq;
     const bool on = j < seq || ((a.anc[(int64_t)m * a.words + (t >> 6)] >> (t & 63)) & 1ull);
     if (on) {
-      const float* kr = j < seq ? a.kc + ((int64_t)bh * S + j) * Dh : a.kt + ((int64_t)bh * M + t) * Dh;
+      const float* kr = j < seq ? a.kc + ((int64_t)kvbh * S + j) * Dh : a.kt + ((int64_t)kvbh * M + t) * Dh;
       float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
       for (int c = 0; c < Dh; c += 4) {
         const float4 kv = *reinterpret_cast<const float4*>(kr + c);
@@ -624,7 +639,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
     for (int u = 0; u < 8; ++u) {
       const int j = min(j0 + 4 * u, nkeys - 1);
       pj[u] = j0 + 4 * u < nkeys ? s_p[j] : 0.f;
-      const float* vr = j < seq ? a.vc + ((int64_t)bh * S + j) * Dh : a.vt + ((int64_t)bh * M + (j - seq)) * Dh;
+      const float* vr = j < seq ? a.vc + ((int64_t)kvbh * S + j) * Dh : a.vt + ((int64_t)kvbh * M + (j - seq)) * Dh;
       v0[u] = vr[lane];
       v1[u] = hi ? vr[lane + 64] : 0.f;
     }
@@ -640,9 +655,16 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
   if (wave == 0) {
     const float o0 = (s_acc[0][lane] + s_acc[1][lane]) + (s_acc[2][lane] + s_acc[3][lane]);
     const float o1 = (s_acc[0][lane + 64] + s_acc[1][lane + 64]) + (s_acc[2][lane + 64] + s_acc[3][lane + 64]);
-    float* orow = a.out + ((int64_t)bh * M + m) * Dh;
-    if (lane < Dh) orow[lane] = o0 / l;
-    if (lane + 64 < Dh) orow[lane + 64] = o1 / l;
+    const int64_t e = ((int64_t)bh * M + m) * Dh;
+    if (a.out_bf16) {
+      __bf16* orow = reinterpret_cast<__bf16*>(a.out) + e;
+      if (lane < Dh) orow[lane] = (__bf16)(o0 / l);
+      if (lane + 64 < Dh) orow[lane + 64] = (__bf16)(o1 / l);
+    } else {
+      float* orow = a.out + e;
+      if (lane < Dh) orow[lane] = o0 / l;
+      if (lane + 64 < Dh) orow[lane + 64] = o1 / l;
+    }
   }
 }
 
@@ -695,8 +717,8 @@ int32_t launch_bf16(const AttnArgs& a, const AttnPlan& p, hipStream_t s) {
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds));
     attr_lds = p.lds;
   }
-  const int BH = a.B * a.H;
-  const unsigned blocks = 8u * ((BH + 7) / 8) * p.nsplit * p.msplits;
+  const int BH = a.B * a.H, KVBH = a.B * a.Hkv;
+  const unsigned blocks = 8u * ((KVBH + 7) / 8) * a.gq * p.nsplit * p.msplits;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(RW * KW * 64), p.lds, s, a);
   LPP_HIP_TRY(hipGetLastError());
   if (p.nsplit > 1 && !a.counters) {
@@ -717,16 +739,20 @@ extern "C" size_t lpp_tree_attention_workspace(const lpp_tree* tree, int32_t B, 
   return lpp_align_up(rows * Dh * sizeof(float), 256) + lpp_align_up(rows * 2 * sizeof(float), 256);
 }
 
-extern "C" int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype, const void* q, const void* k_cache,
-                                      const void* v_cache, const void* k_tree, const void* v_tree,
-                                      const int32_t* seq_len, int32_t B, int32_t H, int32_t S, int32_t Dh,
-                                      float scale, float* out, void* ws, size_t ws_bytes, void* stream) {
+namespace {
+int32_t tree_attention_impl(const lpp_tree* tree, int32_t dtype, int32_t out_dtype, const void* q,
+                            const void* k_cache, const void* v_cache, const void* k_tree, const void* v_tree,
+                            const int32_t* seq_len, int32_t B, int32_t H, int32_t Hkv, int32_t S, int32_t Dh,
+                            float scale, void* out_any, void* ws, size_t ws_bytes, void* stream) {
+  float* out = reinterpret_cast<float*>(out_any);
   if (!tree || !q || !k_tree || !v_tree || !out) return LPP_EINVAL;
   if (B < 1 || H < 1 || S < 0 || Dh < 1) return LPP_EINVAL;
+  if (Hkv < 1 || Hkv > H || H % Hkv != 0) return LPP_EINVAL;
   if (S > 0 && (!k_cache || !v_cache)) return LPP_EINVAL;
   if (scale != scale) return LPP_EINVAL;
   if (Dh != 64 && Dh != 128) return LPP_EUNSUPPORTED;
   if (dtype != LPP_F32 && dtype != LPP_BF16) return LPP_EUNSUPPORTED;
+  if (out_dtype != LPP_F32 && out_dtype != LPP_BF16) return LPP_EUNSUPPORTED;
   if ((int64_t)B * H > (1 << 24) || (int64_t)B * H * H >= (1ll << 32)) return LPP_EUNSUPPORTED;
   if ((int64_t)S * Dh >= (1ll << 31) || (int64_t)tree->M * Dh >= (1ll << 31)) return LPP_EUNSUPPORTED;   // 32-bit offsets inside one head
   const size_t need = lpp_tree_attention_workspace(tree, B, H, S, Dh);
@@ -740,6 +766,7 @@ extern "C" int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype, const
     a.q = (const float*)q; a.kc = (const float*)k_cache; a.vc = (const float*)v_cache;
     a.kt = (const float*)k_tree; a.vt = (const float*)v_tree; a.seq_len = seq_len; a.anc = tree->d_anc;
     a.B = B; a.H = H; a.S = S; a.M = tree->M; a.words = tree->words; a.Dh = Dh; a.scale = scale; a.out = out;
+    a.gq = H / Hkv; a.out_bf16 = out_dtype == LPP_BF16;
     static size_t attr_lds = 48 * 1024;
     const size_t lds = (size_t)(S + tree->M) * sizeof(float);
     if (lds > 144 * 1024) return LPP_EUNSUPPORTED;     // the scores of one row are kept in LDS
@@ -758,10 +785,11 @@ extern "C" int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype, const
   a.q = (const uint16_t*)q; a.kc = (const uint16_t*)k_cache; a.vc = (const uint16_t*)v_cache;
   a.kt = (const uint16_t*)k_tree; a.vt = (const uint16_t*)v_tree; a.seq_len = seq_len; a.anc = tree->d_anc;
   a.B = B; a.H = H; a.S = S; a.M = tree->M; a.words = tree->words;
+  a.Hkv = Hkv; a.gq = H / Hkv; a.out_bf16 = out_dtype == LPP_BF16;
   a.nsplit = p.nsplit; a.msplits = p.msplits; a.mtiles = p.mtiles;
   auto rc = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((0x100000000ull + d - 1) / d); };
   a.rc_perbh = rc((uint32_t)(p.nsplit * p.msplits)); a.rc_msplits = rc((uint32_t)p.msplits);
-  a.rc_H = rc((uint32_t)H); a.rc_nsplit = rc((uint32_t)p.nsplit);
+  a.rc_H = rc((uint32_t)H); a.rc_nsplit = rc((uint32_t)p.nsplit); a.rc_gq = rc((uint32_t)(H / Hkv));
   a.scale_log2 = scale * 1.44269504088896340736f;
   a.out = out;
   a.counters = (int64_t)B * H * p.msplits <= LPP_COUNTER_SLOTS ? tree->d_counters + LPP_COUNTER_SLOTS : nullptr;
@@ -786,4 +814,22 @@ extern "C" int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype, const
   LPP_ATTN(128);
   return LPP_EUNSUPPORTED;
 #undef LPP_ATTN
+}
+}  // namespace
+
+extern "C" int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype, const void* q, const void* k_cache,
+                                      const void* v_cache, const void* k_tree, const void* v_tree,
+                                      const int32_t* seq_len, int32_t B, int32_t H, int32_t S, int32_t Dh,
+                                      float scale, float* out, void* ws, size_t ws_bytes, void* stream) {
+  return tree_attention_impl(tree, dtype, LPP_F32, q, k_cache, v_cache, k_tree, v_tree, seq_len, B, H, H, S, Dh,
+                             scale, out, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t lpp_tree_attention_gqa(const lpp_tree* tree, int32_t dtype, int32_t out_dtype, const void* q,
+                                          const void* k_cache, const void* v_cache, const void* k_tree,
+                                          const void* v_tree, const int32_t* seq_len, int32_t B, int32_t H,
+                                          int32_t Hkv, int32_t S, int32_t Dh, float scale, void* out, void* ws,
+                                          size_t ws_bytes, void* stream) {
+  return tree_attention_impl(tree, dtype, out_dtype, q, k_cache, v_cache, k_tree, v_tree, seq_len, B, H, Hkv, S,
+                             Dh, scale, out, ws, ws_bytes, stream);
 }
