@@ -39,6 +39,11 @@ states holds under the alternatives too, so the choice below is the definition):
     normalised positive part of (adjusted - drafter);
   * siblings are i.i.d. drafter samples tried in index order, each against the
     current residual;
+  (the other reading of each of these two is available as an option of
+  ``relaxed_verify``: ``rule="skip"`` passes over a neighbour that would break the
+  bound and goes on down the list; ``siblings="without_replacement"`` takes a
+  rejected child's token out of the drafter distribution before the next child --
+  pinned by a hand example, a maximality check and exact enumeration of the output law)
   * the tree generator in ``workloads.tree`` (the paper's figure is not text).
 """
 from .knn import build_neighbours, similarity_keys            # noqa: F401

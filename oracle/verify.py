@@ -50,7 +50,8 @@ def _children(parent: np.ndarray) -> List[List[int]]:
 def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits: np.ndarray,
                    vocab_offset: int, V: int, tokens: np.ndarray, neigh: np.ndarray,
                    k: int, lam: float, u_accept: np.ndarray, u_final: np.ndarray,
-                   keep_final_cdf: bool = False, bound: str = "multiplicative") -> Dict[str, np.ndarray]:
+                   keep_final_cdf: bool = False, bound: str = "multiplicative",
+                   rule: str = "prefix", siblings: str = "with_replacement") -> Dict[str, np.ndarray]:
     """target/drafter logits [B,M,ldv]; tokens,u_* [B,M]; neigh [V,>=k] -> dict of outputs.
 
     Outputs (all [B,M] unless noted): decision (uint8), ratio, mass, n_agg,
@@ -62,9 +63,25 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
     ``bound``: "multiplicative" (Sec. 4, LANTERN++: sum_A r < lam * r(x^)) or "additive" (the
     earlier LANTERN bound as Sec. 4 prints it: sum_A r < delta, with ``lam`` holding delta).  In
     both the sum runs over A including x^, and x^ is a member whatever the bound says.
+
+    ``rule``: how A is picked inside B_k(x^), which Sec. 4 leaves to its constraint.  "prefix":
+    the longest nearest-first prefix that keeps the sum below the cap.  "skip": neighbours are
+    visited nearest first, one that would lift the sum to the cap or above is left out and the
+    visit goes on (a maximal set for that order; a superset of the prefix).
+
+    ``siblings``: how the children of one row were drafted (Sec. 2.1 says only that several
+    tokens are sampled from p).  "with_replacement": i.i.d. draws, p is the same for every
+    child.  "without_replacement": the children are distinct tokens drawn one after the other
+    from p with the earlier ones removed; a rejected child's token is therefore taken out of p
+    (p(x^) <- 0, the rest divided by 1 - p(x^)) before the next child is tried.  Both keep the
+    output law equal to the target when A = {x^}.
     """
     if bound not in ("multiplicative", "additive"):
         raise ValueError("bound must be 'multiplicative' or 'additive'")
+    if rule not in ("prefix", "skip"):
+        raise ValueError("rule must be 'prefix' or 'skip'")
+    if siblings not in ("with_replacement", "without_replacement"):
+        raise ValueError("siblings must be 'with_replacement' or 'without_replacement'")
     parent = np.asarray(parent)
     B, M = tokens.shape
     kids = _children(parent)
@@ -100,11 +117,24 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
                     cap = lam * r[t] if bound == "multiplicative" else lam
                     vals = r[np.asarray(nb[:k], dtype=np.int64)]
                     vals[0] = r[t]                       # x^ itself is always a member
-                    C = np.cumsum(vals)                  # nearest-first prefix sums
-                    bad = np.flatnonzero(~(C[1:] < cap)) # strict '<' of the bound
-                    j = 1 + (int(bad[0]) if bad.size else k - 1)
-                    cum = C[j - 1]
-                    seen = C[1:min(j + 1, k)]            # the sums that were compared
+                    if rule == "prefix":
+                        C = np.cumsum(vals)                  # nearest-first prefix sums
+                        bad = np.flatnonzero(~(C[1:] < cap)) # strict '<' of the bound
+                        j = 1 + (int(bad[0]) if bad.size else k - 1)
+                        cum = C[j - 1]
+                        members = np.asarray(nb[1:j], dtype=np.int64)
+                        seen = C[1:min(j + 1, k)]            # the sums that were compared
+                    else:
+                        cum = vals[0]
+                        taken, tried = [], []
+                        for i in range(1, k):                # nearest first; a violator is passed over
+                            tried.append(cum + vals[i])
+                            if cum + vals[i] < cap:
+                                cum = cum + vals[i]
+                                taken.append(int(nb[i]))
+                        j = 1 + len(taken)
+                        members = np.asarray(taken, dtype=np.int64)
+                        seen = np.asarray(tried)
                     if cap > 0 and seen.size:
                         margin[b, c] = np.min(np.abs(seen - cap)) / cap
                     mass[b, c] = cum
@@ -116,12 +146,17 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
                     decision[b, c] = 1 if float(u_accept[b, c]) * p[t] < cum else 0
                     # outcome "c rejected": move A's mass onto x^, take the positive residual
                     r2 = r.copy()
-                    r2[np.asarray(nb[1:j], dtype=np.int64)] = 0.0
+                    r2[members] = 0.0
                     r2[t] = cum
                     res = np.maximum(r2 - p, 0.0)
                     Z = res.sum()
                     if Z > 0:
                         r = res / Z
+                    if siblings == "without_replacement":
+                        left = 1.0 - p[t]                # what the other tokens hold of p
+                        p = p.copy()
+                        p[t] = 0.0
+                        p = p / left if left > 0 else np.zeros_like(p)
             final_all[b, P] = inverse_cdf(r, float(u_final[b, P]))
             if keep_final_cdf:
                 final_cdf[b, P] = np.cumsum(r)

@@ -342,3 +342,119 @@ def test_additive_bound_on_workload_rows():
     with pytest.raises(ValueError):
         relaxed_verify(parent, x["target_logits"], x["drafter_logits"], 0, cfg.V, x["tokens"],
                        neigh, 64, 0.1, x["u_accept"], x["u_final"], bound="other")
+
+
+# ------------------------------------------------- "skip violators" choice of A
+def test_skip_rule_hand_example_and_prefix_comparison():
+    """Worked by hand (Sec. 4 bound, lambda = 3, r(x^) = 0.1 -> cap 0.3), neighbours nearest first
+    with r = 0.15, 0.3, 0.04, 0.2, 0.005:  0.1 + 0.15 = 0.25 fits; + 0.3 does not (skipped);
+    + 0.04 = 0.29 fits; + 0.2 does not; + 0.005 = 0.295 fits.  A = {x^, n1, n3, n5}, mass 0.295;
+    the prefix rule stops at the first violator: A = {x^, n1}, mass 0.25."""
+    q = np.array([0.1, 0.15, 0.3, 0.04, 0.2, 0.005, 0.205])
+    p = np.array([0.5, 0.1, 0.1, 0.1, 0.1, 0.05, 0.05])
+    neigh = np.array([[0, 1, 2, 3, 4, 5, 6]] + [[i] + [j for j in range(7) if j != i] for i in range(1, 7)])
+    kw = dict(keep_final_cdf=True)
+    o = _call([-1, 0], np.stack([q, q]), np.stack([p, p]), [0, 0], neigh, 6, 3.0, [0, 0.55], [0.5, 0.5], rule="skip", **kw)
+    assert o["n_agg"][0, 1] == 4 and o["mass"][0, 1] == pytest.approx(0.295, rel=1e-12)
+    assert o["ratio"][0, 1] == pytest.approx(0.59, rel=1e-12) and o["decision"][0, 1] == 1
+    # residual after a rejection: members n1, n3, n5 hold nothing, x^ holds 0.295
+    adj = np.array([0.295, 0.0, 0.3, 0.0, 0.2, 0.0, 0.205])
+    res = np.clip(adj - p, 0, None)
+    cdf = o["final_cdf"][0, 0]
+    assert np.allclose(np.diff(np.concatenate([[0.0], cdf])) / cdf[-1], res / res.sum(), atol=1e-12)
+    o2 = _call([-1, 0], np.stack([q, q]), np.stack([p, p]), [0, 0], neigh, 6, 3.0, [0, 0.55], [0.5, 0.5])
+    assert o2["n_agg"][0, 1] == 2 and o2["mass"][0, 1] == pytest.approx(0.25, rel=1e-12) and o2["decision"][0, 1] == 0
+
+
+def test_skip_rule_maximal_superset_of_prefix_and_reductions():
+    g = np.random.default_rng(21)
+    V = 9
+    hits = 0
+    for trial in range(60):
+        q = g.dirichlet(np.ones(V) * 0.7); p = g.dirichlet(np.ones(V))
+        lam = float(g.uniform(0.5, 5.0)); k = int(g.integers(1, V + 1))
+        t = int(g.integers(V))
+        neigh = np.array([[i] + [j for j in g.permutation(V) if j != i] for i in range(V)])
+        args = ([-1, 0], np.stack([q, q]), np.stack([p, p]), [0, t], neigh, k, lam, [0, 0.3], [0.1, 0.1])
+        s = _call(*args, rule="skip", keep_final_cdf=True)
+        f = _call(*args)
+        cap = lam * q[t]
+        cdf = s["final_cdf"][0, 0]
+        if lam <= 1 or k == 1:
+            assert s["n_agg"][0, 1] == 1 and s["mass"][0, 1] == pytest.approx(q[t], rel=1e-12)   # Eq. 1
+        assert s["n_agg"][0, 1] >= f["n_agg"][0, 1] and s["mass"][0, 1] >= f["mass"][0, 1] - 1e-15
+        assert s["mass"][0, 1] < cap or s["n_agg"][0, 1] == 1                # the bound of Sec. 4
+        # independent replay: walk the list, a neighbour is out iff adding it to what is in breaks the bound
+        inside, tot = [t], q[t]
+        for j in neigh[t][1:k]:
+            if not (tot + q[j] < cap):
+                continue
+            inside.append(int(j)); tot += q[j]
+        assert s["n_agg"][0, 1] == len(inside) and s["mass"][0, 1] == pytest.approx(tot, rel=1e-12)
+        for j in neigh[t][1:k]:                                               # maximal: nothing left out fits at the end
+            if int(j) not in inside:
+                assert s["mass"][0, 1] + q[j] >= cap * (1 - 1e-12)
+        # the members' mass sits on x^ and nowhere else: the residual's support avoids them
+        resid = np.diff(np.concatenate([[0.0], cdf]))
+        assert all(resid[j] == 0 for j in inside[1:])
+        hits += int(s["n_agg"][0, 1] > f["n_agg"][0, 1])
+    assert hits > 5                                                           # the two rules do differ
+
+
+# ------------------------------------------------- siblings drawn without replacement
+def _first_token_distribution_without_replacement(q, p, n_sib, neigh, k, lam):
+    """Exact law of the first emitted token at a root whose n_sib drafts are distinct tokens,
+    drawn one after the other from p with the earlier draws removed."""
+    V = len(q)
+    parent = [-1] + [0] * n_sib
+    out = np.zeros(V)
+    Q = np.stack([q] * (n_sib + 1)); Pm = np.stack([p] * (n_sib + 1))
+    for toks in itertools.permutations(range(V), n_sib):
+        w, left = 1.0, 1.0
+        for t in toks:                      # probability of drawing this ordered tuple
+            w *= p[t] / left
+            left -= p[t]
+        if w == 0:
+            continue
+        o = _call(parent, Q, Pm, [0] + list(toks), neigh, k, lam, [0.5] * (n_sib + 1),
+                  [0.5] * (n_sib + 1), keep_final_cdf=True, siblings="without_replacement")
+        stay = 1.0
+        for i, t in enumerate(toks):
+            a = min(1.0, o["ratio"][0, i + 1])
+            out[t] += w * stay * a
+            stay *= 1.0 - a
+        cdf = o["final_cdf"][0, 0]
+        out += w * stay * np.diff(np.concatenate([[0.0], cdf])) / cdf[-1]
+    return out
+
+
+@pytest.mark.parametrize("n_sib", [1, 2, 3])
+def test_without_replacement_output_distribution_is_target(n_sib):
+    """Faithfulness (statement after Eq. 2) carries over to distinct drafts when A = {x^}."""
+    g = np.random.default_rng(17 + n_sib)
+    V = 5
+    q = g.dirichlet(np.ones(V)); p = g.dirichlet(np.ones(V))
+    neigh = np.array([np.roll(np.arange(V), -i) for i in range(V)])
+    d = _first_token_distribution_without_replacement(q, p, n_sib, neigh, 1, 3.0)
+    assert abs(d.sum() - 1) < 1e-12 and np.max(np.abs(d - q)) < 1e-12
+    d = _first_token_distribution_without_replacement(q, p, n_sib, neigh, V, 0.9)
+    assert np.max(np.abs(d - q)) < 1e-12
+
+
+def test_without_replacement_drafter_probabilities_and_first_child():
+    g = np.random.default_rng(3)
+    V = 6
+    q = g.dirichlet(np.ones(V)); p = g.dirichlet(np.ones(V))
+    neigh = np.array([[i] + [j for j in range(V) if j != i] for i in range(V)])
+    toks = [0, 4, 1, 3]
+    args = ([-1, 0, 0, 0], np.stack([q] * 4), np.stack([p] * 4), toks, neigh, 3, 2.0, [0, .3, .3, .3], [.2] * 4)
+    a = _call(*args, siblings="without_replacement")
+    b = _call(*args)
+    for f in ("mass", "ratio", "p_tok", "q_tok", "n_agg", "decision"):
+        assert a[f][0, 1] == b[f][0, 1]                                       # the first child sees p itself
+    assert a["p_tok"][0, 2] == pytest.approx(p[1] / (1 - p[4]), rel=1e-12)
+    assert a["p_tok"][0, 3] == pytest.approx(p[3] / (1 - p[4] - p[1]), rel=1e-12)
+    # a token that was already tried has no drafter mass left: certain acceptance if it has any target mass
+    dup = _call([-1, 0, 0], np.stack([q] * 3), np.stack([p] * 3), [0, 2, 2], neigh, 1, 2.0, [0, .99, .99], [.2] * 3,
+                siblings="without_replacement")
+    assert dup["p_tok"][0, 2] == 0.0 and dup["decision"][0, 2] == 1
