@@ -45,7 +45,7 @@ enum { LPP_F32 = 0, LPP_BF16 = 1 };
 /* Limits of this implementation. */
 #define LPP_MAX_ROWS   256     /* M                                     */
 #define LPP_MAX_VOCAB  32768   /* V of lpp_relaxed_verify               */
-#define LPP_MAX_K      4096    /* k of lpp_build_neighbours             */
+#define LPP_MAX_K      4096    /* k of lpp_build_neighbours and verify */
 
 const char* lpp_strerror(int32_t status);   /* static string, never NULL */
 const char* lpp_version(void);
@@ -156,7 +156,7 @@ int32_t lpp_tree_attention_gqa(const lpp_tree* tree, int32_t dtype, int32_t out_
  *             the per-node arrays may be NULL.
  * Errors: LPP_EINVAL (null, B < 1, V < 1, k < 1, k > kstride, k > V,
  * vocab_offset < 0, vocab_offset + V > ldv, lambda NaN), LPP_EUNSUPPORTED
- * (V > LPP_MAX_VOCAB), LPP_ENOWORKSPACE, LPP_EHIP.
+ * (V > LPP_MAX_VOCAB, k > LPP_MAX_K), LPP_ENOWORKSPACE, LPP_EHIP.
  */
 typedef struct lpp_verify_out {
   int32_t* accept_len;     /* [device] [B]        number of accepted drafted nodes            */
@@ -210,6 +210,47 @@ int32_t lpp_relaxed_verify_sampled(const lpp_tree* tree, const float* cond_logit
                                    int32_t kstride, int32_t k, float lambda,
                                    const float* u_accept, const float* u_final,
                                    const lpp_verify_out* out, void* ws, size_t ws_bytes, void* stream);
+
+/* The same step with every choice in one place: the bound (Sec. 4: LANTERN++'s multiplicative
+ * one or the additive one of LANTERN), the front end (App. B "Models"), and the two points the
+ * paper leaves open -- how A is picked inside B_k(x^) (Sec. 4 states only the constraint) and
+ * how the children of one row were drafted (Sec. 2.1: "samples ... tokens" from p):
+ *   rule      LPP_RULE_PREFIX   A = the longest nearest-first prefix of B_k(x^) under the bound
+ *             LPP_RULE_SKIP     neighbours are visited nearest first; one that would lift the
+ *                               sum to the bound or above is passed over and the visit goes on
+ *                               (n_agg = |A| then counts members, not a prefix length)
+ *   siblings  LPP_SIBLINGS_IID       i.i.d. draws from p: every child is tried against p
+ *             LPP_SIBLINGS_DISTINCT  distinct tokens drawn one after the other: a rejected
+ *                               child's token leaves p (p(x^) <- 0, the rest / (1 - p(x^))) before
+ *                               the next child; p_tok and ratio report that p; a token that is
+ *                               handed in twice has p = 0 the second time
+ *   bound, bound_value          LPP_BOUND_MULTIPLICATIVE with lambda, LPP_BOUND_ADDITIVE with delta
+ *   uncond_logits, cfg_scale, top_k   as in lpp_relaxed_verify_sampled; NULL and 0 = no front end
+ * With the zero-initialised struct and bound_value = lambda this is lpp_relaxed_verify.  Both
+ * sibling schemes leave the output law equal to the target when A = {x^}.  Same workspace query;
+ * errors as above, plus LPP_EINVAL for a null opts or an unknown enumerator.
+ */
+#define LPP_BOUND_MULTIPLICATIVE 0
+#define LPP_BOUND_ADDITIVE       1
+#define LPP_RULE_PREFIX          0
+#define LPP_RULE_SKIP            1
+#define LPP_SIBLINGS_IID         0
+#define LPP_SIBLINGS_DISTINCT    1
+typedef struct lpp_verify_options {
+  int32_t bound;
+  float   bound_value;
+  int32_t rule;
+  int32_t siblings;
+  const float* uncond_logits;   /* [device] [B, M, ldv] or NULL */
+  float   cfg_scale;
+  int32_t top_k;
+} lpp_verify_options;
+int32_t lpp_relaxed_verify_opts(const lpp_tree* tree, const float* target_logits,
+                                const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                                int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
+                                int32_t kstride, int32_t k, const lpp_verify_options* opts,
+                                const float* u_accept, const float* u_final,
+                                const lpp_verify_out* out, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------- commit ---
  * Appends what the step keeps to the KV cache (paper App. A.2: accepted tokens are kept, the rest

@@ -68,6 +68,9 @@ def lib() -> C.CDLL:
     L.lpp_relaxed_verify_sampled.restype = i32
     L.lpp_relaxed_verify_sampled.argtypes = [vp, vp, vp, f32, i32, vp, i64, i32, i32, i32, vp, vp, i32, i32, f32, vp, vp,
                                              C.POINTER(VerifyOut), vp, sz, vp]
+    L.lpp_relaxed_verify_opts.restype = i32
+    L.lpp_relaxed_verify_opts.argtypes = [vp, vp, vp, i64, i32, i32, i32, vp, vp, i32, i32, vp, vp, vp,
+                                          C.POINTER(VerifyOut), vp, sz, vp]
     L.lpp_commit_kv.restype = i32
     L.lpp_commit_kv.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
     _lib = L
@@ -168,6 +171,30 @@ def lpp_relaxed_verify_additive(tree: Tree, target_logits, drafter_logits, ldv: 
                                              _ptr(u_accept), _ptr(u_final), C.byref(vo), _ptr(ws),
                                              0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
            "lpp_relaxed_verify_additive")
+
+
+class VerifyOptions(C.Structure):
+    _fields_ = [("bound", C.c_int32), ("bound_value", C.c_float), ("rule", C.c_int32), ("siblings", C.c_int32),
+                ("uncond_logits", C.c_void_p), ("cfg_scale", C.c_float), ("top_k", C.c_int32)]
+
+
+LPP_BOUND_MULTIPLICATIVE, LPP_BOUND_ADDITIVE = 0, 1
+LPP_RULE_PREFIX, LPP_RULE_SKIP = 0, 1
+LPP_SIBLINGS_IID, LPP_SIBLINGS_DISTINCT = 0, 1
+
+
+def lpp_relaxed_verify_opts(tree: Tree, target_logits, drafter_logits, ldv: int, vocab_offset: int, V: int,
+                            B: int, tokens, neigh, kstride: int, k: int, u_accept, u_final, out: dict, ws,
+                            stream=None, *, bound: int = 0, bound_value: float = 0.0, rule: int = 0,
+                            siblings: int = 0, uncond_logits=None, cfg_scale: float = 0.0, top_k: int = 0) -> None:
+    """lpp_relaxed_verify with the bound, the choice of A, the sibling scheme and the front end as options."""
+    vo = VerifyOut(**{n: _ptr(out.get(n)) for n, _ in VerifyOut._fields_})
+    opts = VerifyOptions(bound, bound_value, rule, siblings, _ptr(uncond_logits), cfg_scale, top_k)
+    _check(lib().lpp_relaxed_verify_opts(tree.handle, _ptr(target_logits), _ptr(drafter_logits), ldv, vocab_offset,
+                                         V, B, _ptr(tokens), _ptr(neigh), kstride, k, C.byref(opts),
+                                         _ptr(u_accept), _ptr(u_final), C.byref(vo), _ptr(ws),
+                                         0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
+           "lpp_relaxed_verify_opts")
 
 
 def lpp_commit_kv(tree: Tree, dtype: int, k_tree, v_tree, path, accept_len, seq_len, B: int, H: int, S: int,

@@ -64,6 +64,8 @@ struct VerifyArgs {
   int32_t nstage;         // child lists whose first pass is staged in LDS (<= kMaxStage)
   float lambda;           // bound factor, or delta when `additive`
   int32_t additive;       // 0: sum_A r < lambda r(x^)   1: sum_A r < delta
+  int32_t skip;           // A: 0 longest nearest-first prefix, 1 neighbours that would break the bound are passed over
+  int32_t norepl;         // siblings: 0 i.i.d. draws from p, 1 distinct tokens (a rejected token leaves p)
   const int32_t* tokens;
   const int32_t* neigh;
   const float* u_accept;
@@ -248,7 +250,9 @@ __device__ __forceinline__ float combine_max(const float* s_w, int lane) {
 // owned by wave w.  The neighbour list of a child is taken in passes of 2 NT slots,
 // lane `tid` holding slots 2 tid and 2 tid + 1 of the pass.
 // FRONT: classifier-free guidance and top-k in front of the target softmax (paper App. B "Models").
-template <int NT, int NCH, bool ALIGNED, bool FRONT>
+// ALT: the build that also knows the other readings of A and of the sibling scheme
+// (VerifyArgs::skip, ::norepl); the plain build does not carry their registers and LDS.
+template <int NT, int NCH, bool ALIGNED, bool FRONT, bool ALT>
 __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab tt) {
   constexpr int NW = NT / 64;
   constexpr int NC = NCH * NW;             // cells
@@ -259,6 +263,8 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   extern __shared__ __align__(16) unsigned char smem[];
   float* r_lds = reinterpret_cast<float*>(smem);                              // current r, then the zero cell
   uint32_t* s_neigh = reinterpret_cast<uint32_t*>(r_lds + ZC + 4);            // [nstage][NT] pairs of 16-bit slots
+  float* s_val = reinterpret_cast<float*>(s_neigh + a.nstage * NT);           // ALT: [PASS] gathered values of a pass
+  uint32_t* s_incl = reinterpret_cast<uint32_t*>(s_val + PASS);               // ALT: [PASS / 32] membership bits
   __shared__ float s_max[2][NW];
   __shared__ float s_sum[2][NW];
   __shared__ float s_z[2][NW];
@@ -590,9 +596,13 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
 
   // ---- children in static order, each against the current residual r
   int tog = 0;
+  float pscale = 1.f;        // ALT, distinct siblings: p = p_reg * pscale once rejected tokens have left p
   for (int ci = 0; ci < nchild; ++ci) {
     const int t = s_tok[ci];
     const float rt = r_lds[t];
+    const bool skip_rule = ALT && a.skip;
+    float cum_sk = rt;       // (wave 0) mass of A so far under the skip rule: x^ is always a member
+    int cnt_sk = 0;          // (wave 0) members besides x^
     // bound: sum_A r < lambda * r(x^)  (Sec. 4), or the additive form sum_A r < delta of the same
     // section, brought to the scale of the unnormalised r
     const float cap = a.additive ? a.lambda / rs : a.lambda * rt;
@@ -625,6 +635,41 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
         }
         const int n0 = pk & 0xFFFFu, n1 = pk >> 16;
         const float v0 = r_lds[n0], v1 = r_lds[n1];
+        bool z0, z1;
+        if (skip_rule) {
+          // Neighbours are visited nearest first; one whose value would lift the sum to the cap is
+          // passed over and the visit goes on.  All waves park their values, wave 0 walks them 64
+          // at a time: lanes that cannot fit any more drop out (the sum only grows), a scan over
+          // the rest finds the first that breaks the bound, everything before it joins A.
+          s_val[2 * tid] = v0;
+          s_val[2 * tid + 1] = v1;
+          lds_barrier();
+          if (w == 0) {
+            for (int c = 0; c < PASS / 64; ++c) {
+              const int slot = ps * PASS + 64 * c + lane;
+              if (ps * PASS + 64 * c >= k) break;                       // uniform
+              const float val = s_val[64 * c + lane];
+              unsigned long long rem = __ballot(slot < k && slot != 0), inc = 0ull;
+              for (int it = 0; it < 64 && rem; ++it) {                  // every turn removes at least one lane
+                rem &= __ballot(cum_sk + val < cap);
+                if (!rem) break;
+                const float S = wave_monotone_scan(((rem >> lane) & 1ull) ? val : 0.f);
+                const unsigned long long viol = rem & __ballot(!(cum_sk + S < cap));
+                if (!viol) { inc |= rem; cum_sk = cum_sk + lane_value(S, 63); break; }
+                const int lv = __builtin_amdgcn_readfirstlane(__ffsll((long long)viol) - 1);
+                inc |= rem & ((1ull << lv) - 1ull);
+                cum_sk = cum_sk + lane_value(wave_prev_lane(S, 0.f), lv);
+                rem &= ~((2ull << lv) - 1ull);
+              }
+              cnt_sk += __popcll(inc);
+              if (lane == 0) { s_incl[2 * c] = (uint32_t)inc; s_incl[2 * c + 1] = (uint32_t)(inc >> 32); }
+            }
+          }
+          lds_barrier();
+          const uint32_t bits = s_incl[(2 * tid) >> 5] >> ((2 * tid) & 31);   // (slots of chunks past k: stale bits, masked below)
+          z0 = (bits & 1u) && sl0 < k && sl0 != 0 && n0 != t;
+          z1 = (bits & 2u) && sl0 + 1 < k && n1 != t;
+        } else {
         const float incl = wave_monotone_scan(v0 + v1);
         if (lane == 63) s_wtot[tog][w] = incl;
         lds_barrier();
@@ -646,23 +691,34 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
           s_mass = m0 ? c0 : pc;
           r_lds[t] = m0 ? c0 : pc;                             // A's mass moves onto x^ ...
         }
-        const bool z0 = m0 && sl0 != 0 && n0 != t, z1 = full && n1 != t;
+        z0 = m0 && sl0 != 0 && n0 != t;
+        z1 = full && n1 != t;
+        carry = base;
+        found = !(base < cap);
+        }
         if (z0) r_lds[n0] = 0.f;                               // ... and leaves the other members
         if (z1) r_lds[n1] = 0.f;
         pn[ps] = pk; pv0[ps] = v0; pv1[ps] = v1; pm[ps] = (z0 ? 1u : 0u) | (z1 ? 2u : 0u);
-        carry = base;
-        found = !(base < cap);
       }
     }
-    if (!found && tid == 0) { s_jstar = k; s_mass = carry; r_lds[t] = carry; }
+    if (skip_rule) {
+      if (tid == 0) { s_jstar = 1 + cnt_sk; s_mass = cum_sk; r_lds[t] = cum_sk; }
+    } else if (!found && tid == 0) { s_jstar = k; s_mass = carry; r_lds[t] = carry; }
     if (ci < 8) LPP_TS(4 + 3 * ci);
     lds_barrier();
     if (ci < 8) LPP_TS(5 + 3 * ci);
+    // p(x^): the drafter's probability of the token; with distinct siblings, of what is left of p
+    float pt = 0.f;
+    if (ALT || tid == 0) pt = exp2_fma(s_dlog[ci], md2) * inv_sd;
+    if (ALT && a.norepl) {
+      pt = pt * pscale;
+      for (int cj = 0; cj < ci; ++cj)
+        if (s_tok[cj] == t) pt = 0.f;                           // already tried: it has left p
+    }
     if (tid == 0) {
       const int c = s_child[ci];
       const int jstar = s_jstar;
       const float qt = rt * rs, m = s_mass * rs;
-      const float pt = exp2_fma(s_dlog[ci], md2) * inv_sd;
       const int dec = (s_u[ci] * pt < m) ? 1 : 0;               // u < min(1, mass / p(x^))
       // what the walk needs of this node: a device-scope store, visible to every compute unit
       // once it has completed (no cache write-back needed before the ticket below)
@@ -685,10 +741,17 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       float4* own = reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]);
       rv[j] = *own;
       float4 res;
+      if (ALT) {
+        res.x = __builtin_amdgcn_fmed3f(rv[j].x * rs - p_reg[j][0] * pscale, 0.f, 1.f);
+        res.y = __builtin_amdgcn_fmed3f(rv[j].y * rs - p_reg[j][1] * pscale, 0.f, 1.f);
+        res.z = __builtin_amdgcn_fmed3f(rv[j].z * rs - p_reg[j][2] * pscale, 0.f, 1.f);
+        res.w = __builtin_amdgcn_fmed3f(rv[j].w * rs - p_reg[j][3] * pscale, 0.f, 1.f);
+      } else {
       res.x = __builtin_amdgcn_fmed3f(rv[j].x * rs - p_reg[j][0], 0.f, 1.f);
       res.y = __builtin_amdgcn_fmed3f(rv[j].y * rs - p_reg[j][1], 0.f, 1.f);
       res.z = __builtin_amdgcn_fmed3f(rv[j].z * rs - p_reg[j][2], 0.f, 1.f);
       res.w = __builtin_amdgcn_fmed3f(rv[j].w * rs - p_reg[j][3], 0.f, 1.f);
+      }
       z += (res.x + res.y) + (res.z + res.w);
       *own = res;
     }
@@ -712,6 +775,16 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       }
       if (tid == 0) r_lds[t] = rt;
       lds_barrier();
+    }
+    if (ALT && a.norepl) {
+      // the rejected token leaves p; the rest is divided by what it leaves behind
+#pragma unroll
+      for (int j = 0; j < NCH; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (4 * (tid + NT * j) + e == t) p_reg[j][e] = 0.f;
+      const float left = 1.0f - pt;
+      pscale = left > 0.f ? pscale / left : 0.f;
     }
   }
 
@@ -822,11 +895,12 @@ __global__ __launch_bounds__(64) void walk_kernel(VerifyArgs a) {
             a.accept_len + b, a.path + (int64_t)b * a.depth, a.final_token + b);
 }
 
-template <int NT, int NCH, bool ALIGNED, bool FRONT>
+template <int NT, int NCH, bool ALIGNED, bool FRONT, bool ALT>
 int32_t launch_rows(const VerifyArgs& a, const TreeTab& tt, hipStream_t stream) {
   static size_t attr_lds = 0;   // largest dynamic LDS size this instantiation was enabled for
-  const size_t lds = ((size_t)NT * NCH * 4 + 4) * sizeof(float) + (size_t)a.nstage * NT * sizeof(uint32_t);
-  auto kern = verify_rows_kernel<NT, NCH, ALIGNED, FRONT>;
+  const size_t lds = ((size_t)NT * NCH * 4 + 4) * sizeof(float) + (size_t)a.nstage * NT * sizeof(uint32_t) +
+                     (ALT ? (size_t)2 * NT * sizeof(float) + (size_t)2 * NT / 8 : 0);
+  auto kern = verify_rows_kernel<NT, NCH, ALIGNED, FRONT, ALT>;
   if (lds > attr_lds) {
     LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -847,7 +921,8 @@ extern "C" size_t lpp_relaxed_verify_workspace(const lpp_tree* tree, int32_t B, 
 }
 
 namespace {
-int32_t relaxed_verify_impl(int32_t additive, bool front, const float* uncond_logits, float cfg_scale,
+int32_t relaxed_verify_impl(int32_t additive, int32_t skip, int32_t norepl, bool front,
+                            const float* uncond_logits, float cfg_scale,
                             int32_t top_k, const lpp_tree* tree, const float* target_logits,
                             const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
                             int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
@@ -860,7 +935,7 @@ int32_t relaxed_verify_impl(int32_t additive, bool front, const float* uncond_lo
   if (B < 1 || V < 1 || k < 1 || k > kstride || k > V) return LPP_EINVAL;
   if (vocab_offset < 0 || (int64_t)vocab_offset + V > ldv) return LPP_EINVAL;
   if (lambda != lambda) return LPP_EINVAL;
-  if (V > LPP_MAX_VOCAB) return LPP_EUNSUPPORTED;
+  if (V > LPP_MAX_VOCAB || k > LPP_MAX_K) return LPP_EUNSUPPORTED;
   if ((int64_t)B * tree->M > INT_MAX) return LPP_EUNSUPPORTED;
   const size_t need = lpp_relaxed_verify_workspace(tree, B, V, k);
   if (!ws || ws_bytes < need) return LPP_ENOWORKSPACE;
@@ -870,6 +945,8 @@ int32_t relaxed_verify_impl(int32_t additive, bool front, const float* uncond_lo
   a.target = target_logits; a.uncond = uncond_logits; a.cfg_scale = cfg_scale; a.top_k = top_k;
   a.drafter = drafter_logits; a.ldv = ldv; a.off = vocab_offset;
   a.V = V; a.M = tree->M; a.B = B; a.kstride = kstride; a.k = k; a.lambda = lambda; a.additive = additive;
+  a.skip = skip; a.norepl = norepl;
+  const bool alt = skip || norepl;
   a.depth = tree->depth > 0 ? tree->depth : 1;
   // Staged lists cost LDS.  When there are several rows per compute unit, two rows resident at
   // once (one computing while the other's loads are in flight) are worth more than staging the
@@ -909,15 +986,20 @@ int32_t relaxed_verify_impl(int32_t additive, bool front, const float* uncond_lo
   };
   const bool al = aligned16(target_logits) && aligned16(drafter_logits) && aligned16(uncond_logits);
   int32_t st;
-#define LPP_DISPATCH(T, N)                                                                          \
-  st = front ? (al ? launch_rows<T, N, true, true>(a, tt, s) : launch_rows<T, N, false, true>(a, tt, s))  \
-             : (al ? launch_rows<T, N, true, false>(a, tt, s) : launch_rows<T, N, false, false>(a, tt, s))
+#define LPP_DISPATCH2(T, N, ALT)                                                                            \
+  st = front ? (al ? launch_rows<T, N, true, true, ALT>(a, tt, s) : launch_rows<T, N, false, true, ALT>(a, tt, s))   \
+             : (al ? launch_rows<T, N, true, false, ALT>(a, tt, s) : launch_rows<T, N, false, false, ALT>(a, tt, s))
+#define LPP_DISPATCH(T, N)                                     \
+  do {                                                         \
+    if (alt) { LPP_DISPATCH2(T, N, true); } else { LPP_DISPATCH2(T, N, false); } \
+  } while (0)
   if (V <= 2048) LPP_DISPATCH(512, 1);
   else if (V <= 4096) LPP_DISPATCH(512, 2);
   else if (V <= 8192) LPP_DISPATCH(512, 4);
   else if (V <= 16384) LPP_DISPATCH(512, 8);
   else LPP_DISPATCH(1024, 8);
 #undef LPP_DISPATCH
+#undef LPP_DISPATCH2
   if (st != LPP_OK) return st;
   if (!fused_walk) {
     hipLaunchKernelGGL(walk_kernel, dim3((unsigned)B), dim3(64), 0, s, a);
@@ -933,7 +1015,7 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
                                       int32_t kstride, int32_t k, float lambda, const float* u_accept,
                                       const float* u_final, const lpp_verify_out* out, void* ws,
                                       size_t ws_bytes, void* stream) {
-  return relaxed_verify_impl(0, false, nullptr, 0.f, 0, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
+  return relaxed_verify_impl(0, 0, 0, false, nullptr, 0.f, 0, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
                              kstride, k, lambda, u_accept, u_final, out, ws, ws_bytes, stream);
 }
 
@@ -944,7 +1026,7 @@ extern "C" int32_t lpp_relaxed_verify_additive(const lpp_tree* tree, const float
                                                const float* u_accept, const float* u_final,
                                                const lpp_verify_out* out, void* ws, size_t ws_bytes,
                                                void* stream) {
-  return relaxed_verify_impl(1, false, nullptr, 0.f, 0, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
+  return relaxed_verify_impl(1, 0, 0, false, nullptr, 0.f, 0, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
                              kstride, k, delta, u_accept, u_final, out, ws, ws_bytes, stream);
 }
 
@@ -956,7 +1038,25 @@ extern "C" int32_t lpp_relaxed_verify_sampled(const lpp_tree* tree, const float*
                                               const float* u_final, const lpp_verify_out* out, void* ws,
                                               size_t ws_bytes, void* stream) {
   if (cfg_scale != cfg_scale || top_k < 0) return LPP_EINVAL;
-  return relaxed_verify_impl(0, true, uncond_logits, cfg_scale, top_k, tree, cond_logits, drafter_logits, ldv,
+  return relaxed_verify_impl(0, 0, 0, true, uncond_logits, cfg_scale, top_k, tree, cond_logits, drafter_logits, ldv,
                              vocab_offset, V, B, tokens, neigh, kstride, k, lambda, u_accept, u_final, out, ws,
                              ws_bytes, stream);
+}
+
+extern "C" int32_t lpp_relaxed_verify_opts(const lpp_tree* tree, const float* target_logits,
+                                           const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                                           int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
+                                           int32_t kstride, int32_t k, const lpp_verify_options* opts,
+                                           const float* u_accept, const float* u_final,
+                                           const lpp_verify_out* out, void* ws, size_t ws_bytes, void* stream) {
+  if (!opts) return LPP_EINVAL;
+  if (opts->bound != LPP_BOUND_MULTIPLICATIVE && opts->bound != LPP_BOUND_ADDITIVE) return LPP_EINVAL;
+  if (opts->rule != LPP_RULE_PREFIX && opts->rule != LPP_RULE_SKIP) return LPP_EINVAL;
+  if (opts->siblings != LPP_SIBLINGS_IID && opts->siblings != LPP_SIBLINGS_DISTINCT) return LPP_EINVAL;
+  if (opts->cfg_scale != opts->cfg_scale || opts->top_k < 0) return LPP_EINVAL;
+  const bool front = opts->uncond_logits != nullptr || opts->top_k > 0;
+  return relaxed_verify_impl(opts->bound == LPP_BOUND_ADDITIVE, opts->rule == LPP_RULE_SKIP,
+                             opts->siblings == LPP_SIBLINGS_DISTINCT, front, opts->uncond_logits, opts->cfg_scale,
+                             opts->top_k, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
+                             kstride, k, opts->bound_value, u_accept, u_final, out, ws, ws_bytes, stream);
 }

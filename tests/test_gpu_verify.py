@@ -38,7 +38,7 @@ def test_verify_parity_lumina_like_strided_rows():
 
 def test_verify_parity_stress_full_batch():
     rep, got = _case(CONFIGS[5], 0.8)
-    assert rep["nodes"] + rep["nagg_ties"] + rep["skipped_after_tie"] == 16 * 128
+    assert rep["nodes"] + rep["skipped_after_tie"] == 16 * 128        # (nodes counts the tied ones too)
     assert got["accept_len"].max() >= 2
 
 
