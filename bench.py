@@ -47,6 +47,10 @@ def main():
     ap.add_argument("--frontend", action="store_true",
                     help="verify through lpp_relaxed_verify_sampled (guidance 3.0 + top-k 2000 fused; reads one more "
                          "target row set); not the headline configuration")
+    ap.add_argument("--rule", choices=["prefix", "skip"], default="prefix",
+                    help="choice of A inside B_k (lpp_relaxed_verify_opts when not the default)")
+    ap.add_argument("--siblings", choices=["iid", "distinct"], default="iid",
+                    help="sibling scheme (lpp_relaxed_verify_opts when not the default)")
     ap.add_argument("--layers", type=int, default=1,
                     help="attention launches per step, each on its own K/V cache (a target's layer count); "
                          "the headline step has one")
@@ -181,7 +185,16 @@ def main():
 
     def verify(d, st=None):
         st = stream if st is None else st
-        if args.frontend:
+        if args.rule != "prefix" or args.siblings != "iid":
+            lpp.lpp_relaxed_verify_opts(tree, d["target_logits"], d["drafter_logits"], cfg.ldv, cfg.vocab_offset, V, B,
+                                        d["tokens"], neigh, k, k, d["u_accept"], d["u_final"], d["vout"], ver_ws, st,
+                                        bound=lpp.LPP_BOUND_MULTIPLICATIVE, bound_value=cfg.lam,
+                                        rule=lpp.LPP_RULE_SKIP if args.rule == "skip" else lpp.LPP_RULE_PREFIX,
+                                        siblings=lpp.LPP_SIBLINGS_DISTINCT if args.siblings == "distinct"
+                                        else lpp.LPP_SIBLINGS_IID,
+                                        uncond_logits=d["uncond_logits"] if args.frontend else None,
+                                        cfg_scale=3.0 if args.frontend else 0.0, top_k=2000 if args.frontend else 0)
+        elif args.frontend:
             lpp.lpp_relaxed_verify_sampled(tree, d["target_logits"], d["uncond_logits"], 3.0, 2000, d["drafter_logits"],
                                            cfg.ldv, cfg.vocab_offset, V, B, d["tokens"], neigh, k, k, cfg.lam,
                                            d["u_accept"], d["u_final"], d["vout"], ver_ws, st)
@@ -311,6 +324,7 @@ def main():
            "config": {"workload": f"config {cfg.idx} ({cfg.name}): B={B} H={H}x{Dh} S={S} M={M} V={V} k={k} "
                                   f"lambda={cfg.lam}", "replicas_rotated": R, "mean_accept_len": mean_accept,
                       "frontend": "cfg 3.0 + top-k 2000 fused" if args.frontend else "none (final logits handed in)",
+                      "rule": args.rule, "siblings": args.siblings,
                       "attention_layers_per_step": L, "kv_heads": Hkv,
                       "attention_out": "bf16" if args.out_bf16 else "f32",
                       "launch": launch},
