@@ -22,6 +22,8 @@
 #include <limits.h>
 #include <math.h>
 
+#include <type_traits>
+
 #include "lpp_internal.h"
 
 namespace {
@@ -80,13 +82,6 @@ __global__ __launch_bounds__(256) void knn_pack_kernel(KnnArgs a) {
     atomicMax(a.maxnorm, __float_as_uint(fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]))));
 }
 
-__device__ __forceinline__ int sim_bin(float s) {
-  const float x = (s + 1.0f) * kBinScale;
-  int b = (int)floorf(x);
-  b = x != x ? 0 : b;
-  return min(max(b, 0), kBins - 1);
-}
-
 // NS4 = float4 loads per lane and code (DP = 16 * NS4).  Contraction slot (step, g)
 // of the 16x16x4 MFMA is dimension 16*(step/4) + 4*g + step%4 on both operands.
 // A block owns 16 query codes; its 4 waves take the code tiles (16 codes each) in turn and share
@@ -115,14 +110,22 @@ __global__ __launch_bounds__(kSelWaves * 64) void knn_select_kernel(KnnArgs a) {
   if (threadIdx.x < kSelRows) s_cnt[threadIdx.x] = 0;
   __syncthreads();
 
-  int bstar = 0;
-  for (int phase = 0; phase < 2; ++phase) {
+  float thr = 0.f;          // second sweep: candidates are the codes with x >= thr (bin >= b* - 1) ...
+  bool take_all = true;     // ... or all of them when b* - 1 <= 0 (bin 0 also holds NaN)
+  const float* lane_row = a.Ep + (int64_t)l16 * DP + 4 * g4;
+  uint32_t* my_hist = s_hist + l16 * (kBins / 2);
+  // One sweep over all code tiles.  PHASE 0 histograms, PHASE 1 appends.  x = (s + 1) * 512 is the bin
+  // before truncation; bin >= b is x >= b (the map is monotone), so the second sweep compares floats.
+  // Tiles that hold the query's own code or padding take a checked path; the others have no branch
+  // per similarity.
+  auto sweep = [&](auto phase_tag) {
+    constexpr int PHASE = decltype(phase_tag)::value;
     for (int t0 = wave; t0 < ntiles; t0 += kSelWaves * U) {
       f32x4 av[U][NS4];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int t = min(t0 + kSelWaves * u, ntiles - 1);      // (past the end: a re-read that is not used)
-        const float* arow = a.Ep + (int64_t)(t * 16 + l16) * DP + 4 * g4;
+        const float* arow = lane_row + (int64_t)t * (16 * DP);
 #pragma unroll
         for (int s = 0; s < NS4; ++s) av[u][s] = *reinterpret_cast<const f32x4*>(arow + 16 * s);
       }
@@ -136,24 +139,45 @@ __global__ __launch_bounds__(kSelWaves * 64) void knn_select_kernel(KnnArgs a) {
           acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][s][2], qv[s][2], acc0, 0, 0, 0);
           acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][s][3], qv[s][3], acc1, 0, 0, 0);
         }
-        const f32x4 acc = acc0 + acc1;
         const int t = t0 + kSelWaves * u;
         if (t >= ntiles) continue;
         // lane holds sim(code 16 t + 4*g4 + r, query qrow), r = 0..3
+        float x[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int code = t * 16 + 4 * g4 + r;
-          if (code >= V || code == qrow || qrow >= V) continue;
-          const int bin = sim_bin(acc[r]);
-          if (phase == 0) {
-            atomicAdd(&s_hist[l16 * (kBins / 2) + (bin >> 1)], (bin & 1) ? 65536u : 1u);
-          } else if (bin >= bstar - 1) {
-            const int pos = atomicAdd(&s_cnt[l16], 1);
-            if (pos < a.cap) a.cand[(int64_t)qrow * a.cap + pos] = (uint16_t)code;
+        for (int r = 0; r < 4; ++r) x[r] = __builtin_fmaf(acc0[r] + acc1[r], kBinScale, kBinScale);
+        const bool plain = t != row0 / 16 && t * 16 + 16 <= V && row0 + kSelRows <= V;    // uniform
+        if (PHASE == 0) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int code = t * 16 + 4 * g4 + r;
+            const int bin = min(max((int)x[r], 0), kBins - 1);      // (int) truncates and sends NaN to 0
+            if (plain || !(code >= V || code == qrow || qrow >= V))
+              atomicAdd(&my_hist[bin >> 1], 1u << ((bin & 1) << 4));
+          }
+        } else {
+          bool pass[4];
+          bool any = false;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int code = t * 16 + 4 * g4 + r;
+            pass[r] = (take_all || x[r] >= thr) && (plain || !(code >= V || code == qrow || qrow >= V));
+            any = any || pass[r];
+          }
+          if (__ballot(any)) {                                      // about one code in sixteen passes
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (pass[r]) {
+                const int pos = atomicAdd(&s_cnt[l16], 1);
+                if (pos < a.cap) a.cand[(int64_t)qrow * a.cap + pos] = (uint16_t)(t * 16 + 4 * g4 + r);
+              }
           }
         }
       }
     }
+  };
+  for (int phase = 0; phase < 2; ++phase) {
+    if (phase == 0) sweep(std::integral_constant<int, 0>());
+    else sweep(std::integral_constant<int, 1>());
     __syncthreads();
     if (phase == 0) {
       // b* of each row: highest bin whose count-from-the-top reaches kk; a wave takes 4 of the 16 rows
@@ -197,7 +221,8 @@ __global__ __launch_bounds__(kSelWaves * 64) void knn_select_kernel(KnnArgs a) {
         }
       }
       __syncthreads();
-      bstar = s_bstar[l16];
+      thr = (float)(s_bstar[l16] - 1);
+      take_all = s_bstar[l16] - 1 <= 0;
     }
   }
   if (threadIdx.x < kSelRows && row0 + threadIdx.x < a.Vp) a.cnt[row0 + threadIdx.x] = s_cnt[threadIdx.x];
@@ -412,7 +437,7 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
     const int bs = a.bstar[i];
     if (bs - 1 >= 1) {
       const float edge = (float)(bs - 1) / kBinScale - 1.0f;      // lower edge of bin b* - 1
-      const float eps = (float)(DP + 4) * 1.1920929e-07f * a.norms[i] * __uint_as_float(*a.maxnorm) * 1.001f + 1e-37f;
+      const float eps = (float)(DP + 4) * 1.1920929e-07f * a.norms[i] * __uint_as_float(*a.maxnorm) * 1.001f + 2.5e-7f;   // (+ the rounding of the bin map itself)
       slow = s_kth < orderable((double)edge + (double)eps);
     }
     if (!slow) return;
