@@ -58,7 +58,13 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
     q_tok, p_tok, final_tok_all; accept_len [B], path [B,depth] (-1 padded),
     final_token [B].  Diagnostics: bound_margin = min_j |cum_j - lam*r(x^)| /
     (lam*r(x^)) over the prefix sums that were compared (inf if none);
-    final_cdf [B,M,V] (cumulative, unnormalised) if requested.
+    final_cdf [B,M,V] (cumulative, unnormalised) if requested;
+    mass_err, q_tok_err, p_tok_err = first-order bounds on the absolute error that an
+    implementation working in float32 can have in mass, q_tok, p_tok: Eq. 2 subtracts p from
+    the adjusted target, and where the two nearly cancel (a sibling that repeats a token
+    whose adjusted target mass is close to p) what is left carries the rounding of both
+    operands, divided by the normaliser.  The bound is carried through the siblings with
+    2^-22 per value (a few float32 roundings) as the unit.
 
     ``bound``: "multiplicative" (Sec. 4, LANTERN++: sum_A r < lam * r(x^)) or "additive" (the
     earlier LANTERN bound as Sec. 4 prints it: sum_A r < delta, with ``lam`` holding delta).  In
@@ -97,6 +103,8 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
     q_tok = np.zeros((B, M)); p_tok = np.zeros((B, M))
     n_agg = np.zeros((B, M), dtype=np.int32)
     margin = np.full((B, M), np.inf)
+    mass_err = np.zeros((B, M)); q_tok_err = np.zeros((B, M)); p_tok_err = np.zeros((B, M))
+    eps = 2.0 ** -22
     final_all = np.zeros((B, M), dtype=np.int32)
     accept_len = np.zeros(B, dtype=np.int32)
     path = np.full((B, max(max_depth, 1)), -1, dtype=np.int32)
@@ -111,6 +119,8 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
             r = q.copy()
             if kids[P]:
                 p = softmax64(drafter_logits[b, P])[off:off + V]
+                r_err = eps * r                      # bound on the float32 error of each r(x) ...
+                p_err = eps * p                      # ... and p(x)
                 for c in kids[P]:
                     t = int(tokens[b, c])
                     nb = neigh[t]
@@ -138,6 +148,9 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
                     if cap > 0 and seen.size:
                         margin[b, c] = np.min(np.abs(seen - cap)) / cap
                     mass[b, c] = cum
+                    mass_err[b, c] = r_err[t] + r_err[members].sum()
+                    q_tok_err[b, c] = r_err[t]
+                    p_tok_err[b, c] = p_err[t]
                     n_agg[b, c] = j
                     q_tok[b, c] = r[t]
                     p_tok[b, c] = p[t]
@@ -151,12 +164,26 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
                     res = np.maximum(r2 - p, 0.0)
                     Z = res.sum()
                     if Z > 0:
+                        e2 = r_err.copy()
+                        e2[members] = 0.0
+                        e2[t] = mass_err[b, c]
+                        d_err = e2 + p_err + eps * (r2 + p)          # error of r2 - p before the clamp
+                        live = (res > 0) | (np.abs(r2 - p) <= d_err)  # entries that are, or could be, positive
+                        z_err = d_err[live].sum()
                         r = res / Z
+                        r_err = np.where(live, d_err, 0.0) / Z + r * (z_err / Z) + eps * r
                     if siblings == "without_replacement":
                         left = 1.0 - p[t]                # what the other tokens hold of p
+                        left_err = p_err[t] + eps
                         p = p.copy()
                         p[t] = 0.0
-                        p = p / left if left > 0 else np.zeros_like(p)
+                        if left > 0:
+                            p = p / left
+                            p_err = p_err / left + p * (left_err / left) + eps * p
+                            p_err[t] = 0.0
+                        else:
+                            p = np.zeros_like(p)
+                            p_err = np.zeros_like(p)
             final_all[b, P] = inverse_cdf(r, float(u_final[b, P]))
             if keep_final_cdf:
                 final_cdf[b, P] = np.cumsum(r)
@@ -174,7 +201,7 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
     out = {"decision": decision, "ratio": ratio, "mass": mass, "n_agg": n_agg,
            "q_tok": q_tok, "p_tok": p_tok, "final_tok_all": final_all,
            "accept_len": accept_len, "path": path, "final_token": final_token,
-           "bound_margin": margin}
+           "bound_margin": margin, "mass_err": mass_err, "q_tok_err": q_tok_err, "p_tok_err": p_tok_err}
     if keep_final_cdf:
         out["final_cdf"] = final_cdf
     return out

@@ -896,10 +896,16 @@ __global__ __launch_bounds__(64) void walk_kernel(VerifyArgs a) {
 }
 
 template <int NT, int NCH, bool ALIGNED, bool FRONT, bool ALT>
-int32_t launch_rows(const VerifyArgs& a, const TreeTab& tt, hipStream_t stream) {
+int32_t launch_rows(const VerifyArgs& a_in, const TreeTab& tt, hipStream_t stream) {
   static size_t attr_lds = 0;   // largest dynamic LDS size this instantiation was enabled for
-  const size_t lds = ((size_t)NT * NCH * 4 + 4) * sizeof(float) + (size_t)a.nstage * NT * sizeof(uint32_t) +
-                     (ALT ? (size_t)2 * NT * sizeof(float) + (size_t)2 * NT / 8 : 0);
+  VerifyArgs a = a_in;
+  auto lds_for = [](int nstage) {
+    return ((size_t)NT * NCH * 4 + 4) * sizeof(float) + (size_t)nstage * NT * sizeof(uint32_t) +
+           (ALT ? (size_t)2 * NT * sizeof(float) + (size_t)2 * NT / 8 : 0);
+  };
+  // 160 KB per compute unit, less the kernel's fixed arrays: the widest rows keep fewer lists staged
+  while (a.nstage > 0 && lds_for(a.nstage) > 152 * 1024) --a.nstage;
+  const size_t lds = lds_for(a.nstage);
   auto kern = verify_rows_kernel<NT, NCH, ALIGNED, FRONT, ALT>;
   if (lds > attr_lds) {
     LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

@@ -65,7 +65,8 @@ def compare_verify(parent, x, neigh, V, off, k, lam, got, rel=1e-4, tie=1e-5, cd
     """Compare every output with the float64 oracle.  Returns a report dict.
 
     Rules: decisions bit-exact unless |u - ratio| < tie (counted); mass / ratio /
-    q_tok / p_tok within rel; n_agg equal unless the oracle's bound margin shows a
+    q_tok / p_tok within rel, plus the oracle's bound on what float32 loses where the
+    residual's subtraction cancels (2^-22 relative for ordinary nodes); n_agg equal unless the oracle's bound margin shows a
     float32-level tie at the stopping sum (counted); after such a tie the later
     siblings and the parent's draw are not comparable and are skipped (counted);
     final tokens must bracket u*Z in the oracle's float64 CDF within cdf_tol*Z.
@@ -104,8 +105,15 @@ def compare_verify(parent, x, neigh, V, off, k, lam, got, rel=1e-4, tie=1e-5, cd
                     if g == w or (np.isnan(g) and np.isnan(w)):     # also +inf (p = 0) and 0/0 (p = 0 and no mass)
                         continue
                     err = abs(g - w) / max(abs(w), 1e-300)
-                    rep["max_rel"] = max(rep["max_rel"], err)
-                    assert err <= rel, f"{name} b={b} c={c}: got {g} want {w} rel {err}"
+                    # what float32 can lose where Eq. 2's subtraction nearly cancels (the oracle's own bound)
+                    pt = max(float(want["p_tok"][b, c]), 1e-300)
+                    slack = {"mass": want["mass_err"][b, c], "q_tok": want["q_tok_err"][b, c],
+                             "p_tok": want["p_tok_err"][b, c],
+                             "ratio": want["mass_err"][b, c] / pt + abs(w) * want["p_tok_err"][b, c] / pt}[name]
+                    if abs(g - w) <= rel * abs(w) + float(slack):
+                        rep["max_rel"] = max(rep["max_rel"], min(err, rel))
+                        continue
+                    assert err <= rel, f"{name} b={b} c={c}: got {g} want {w} rel {err} slack {slack}"
                 if got["decision"][b, c] != want["decision"][b, c]:
                     u = float(x["u_accept"][b, c])
                     assert abs(u - want["ratio"][b, c]) < tie, (
