@@ -670,31 +670,31 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
           z0 = (bits & 1u) && sl0 < k && sl0 != 0 && n0 != t;
           z1 = (bits & 2u) && sl0 + 1 < k && n1 != t;
         } else {
-        const float incl = wave_monotone_scan(v0 + v1);
-        if (lane == 63) s_wtot[tog][w] = incl;
-        lds_barrier();
-        float base = carry, mybase = carry;
+          const float incl = wave_monotone_scan(v0 + v1);
+          if (lane == 63) s_wtot[tog][w] = incl;
+          lds_barrier();
+          float base = carry, mybase = carry;
 #pragma unroll
-        for (int i = 0; i < NW; ++i) {
-          if (i == w) mybase = base;
-          base += s_wtot[tog][i];
-        }
-        tog ^= 1;
-        const float G = mybase + incl;                         // through my slots
-        const float pc = mybase + wave_prev_lane(incl, 0.f);   // before my slots
-        const bool full = G < cap;
-        const bool edge = !full && (pc < cap || sl0 == 0);     // A ends in my slots
-        const float c0 = pc + v0;
-        const bool m0 = full || (edge && (sl0 == 0 || c0 < cap));
-        if (edge) {
-          s_jstar = min(m0 ? sl0 + 1 : sl0, k);
-          s_mass = m0 ? c0 : pc;
-          r_lds[t] = m0 ? c0 : pc;                             // A's mass moves onto x^ ...
-        }
-        z0 = m0 && sl0 != 0 && n0 != t;
-        z1 = full && n1 != t;
-        carry = base;
-        found = !(base < cap);
+          for (int i = 0; i < NW; ++i) {
+            if (i == w) mybase = base;
+            base += s_wtot[tog][i];
+          }
+          tog ^= 1;
+          const float G = mybase + incl;                         // through my slots
+          const float pc = mybase + wave_prev_lane(incl, 0.f);   // before my slots
+          const bool full = G < cap;
+          const bool edge = !full && (pc < cap || sl0 == 0);     // A ends in my slots
+          const float c0 = pc + v0;
+          const bool m0 = full || (edge && (sl0 == 0 || c0 < cap));
+          if (edge) {
+            s_jstar = min(m0 ? sl0 + 1 : sl0, k);
+            s_mass = m0 ? c0 : pc;
+            r_lds[t] = m0 ? c0 : pc;                             // A's mass moves onto x^ ...
+          }
+          z0 = m0 && sl0 != 0 && n0 != t;
+          z1 = full && n1 != t;
+          carry = base;
+          found = !(base < cap);
         }
         if (z0) r_lds[n0] = 0.f;                               // ... and leaves the other members
         if (z1) r_lds[n1] = 0.f;
@@ -747,10 +747,10 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
         res.z = __builtin_amdgcn_fmed3f(rv[j].z * rs - p_reg[j][2] * pscale, 0.f, 1.f);
         res.w = __builtin_amdgcn_fmed3f(rv[j].w * rs - p_reg[j][3] * pscale, 0.f, 1.f);
       } else {
-      res.x = __builtin_amdgcn_fmed3f(rv[j].x * rs - p_reg[j][0], 0.f, 1.f);
-      res.y = __builtin_amdgcn_fmed3f(rv[j].y * rs - p_reg[j][1], 0.f, 1.f);
-      res.z = __builtin_amdgcn_fmed3f(rv[j].z * rs - p_reg[j][2], 0.f, 1.f);
-      res.w = __builtin_amdgcn_fmed3f(rv[j].w * rs - p_reg[j][3], 0.f, 1.f);
+        res.x = __builtin_amdgcn_fmed3f(rv[j].x * rs - p_reg[j][0], 0.f, 1.f);
+        res.y = __builtin_amdgcn_fmed3f(rv[j].y * rs - p_reg[j][1], 0.f, 1.f);
+        res.z = __builtin_amdgcn_fmed3f(rv[j].z * rs - p_reg[j][2], 0.f, 1.f);
+        res.w = __builtin_amdgcn_fmed3f(rv[j].w * rs - p_reg[j][3], 0.f, 1.f);
       }
       z += (res.x + res.y) + (res.z + res.w);
       *own = res;
