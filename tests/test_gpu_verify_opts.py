@@ -97,3 +97,40 @@ def test_opts_argument_errors():
         with pytest.raises(lpp.LppError) as e:
             run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam, opts=bad)
         assert e.value.status == lpp.LPP_EINVAL
+
+
+@pytest.mark.parametrize("additive,lam", [(False, 3.0), (True, 0.05)])
+def test_opts_everything_at_once_front_end_skip_rule_distinct_siblings(additive, lam):
+    """Guidance + top-k in front, the skip rule and distinct siblings behind, either bound: the oracle
+    pipeline is sampling_frontend -> relaxed_verify with the same options."""
+    from oracle import sampling_frontend
+    from gpu_common import DEV, dev
+    cfg = CONFIGS[3].scaled(B=2)
+    parent = static_tree(cfg.branching, cfg.N)
+    tree = lpp.Tree(parent)
+    x = make_verify_inputs(cfg, parent, rho=0.8, salt=3)
+    y = make_verify_inputs(cfg, parent, rho=0.0, salt=103)
+    V, off, k = cfg.V, cfg.vocab_offset, cfg.k
+    B, M = x["tokens"].shape
+    neigh = sparse_neighbour_table(make_codebook(cfg), k, x["tokens"][:, 1:], V)
+    out = {"accept_len": torch.full((B,), -7, dtype=torch.int32, device=DEV),
+           "path": torch.full((B, max(tree.depth, 1)), -7, dtype=torch.int32, device=DEV),
+           "final_token": torch.full((B,), -7, dtype=torch.int32, device=DEV),
+           "decision": torch.full((B, M), 9, dtype=torch.uint8, device=DEV),
+           "ratio": torch.zeros((B, M), device=DEV), "mass": torch.zeros((B, M), device=DEV),
+           "n_agg": torch.zeros((B, M), dtype=torch.int32, device=DEV),
+           "q_tok": torch.zeros((B, M), device=DEV), "p_tok": torch.zeros((B, M), device=DEV),
+           "final_tok_all": torch.full((B, M), -7, dtype=torch.int32, device=DEV)}
+    ws = torch.empty(lpp.lpp_relaxed_verify_workspace(tree, B, V, k), dtype=torch.uint8, device=DEV)
+    lpp.lpp_relaxed_verify_opts(tree, dev(x["target_logits"]), dev(x["drafter_logits"]), cfg.ldv, off, V, B,
+                                dev(x["tokens"]), dev(neigh), neigh.shape[1], k, dev(x["u_accept"]), dev(x["u_final"]),
+                                out, ws, bound=lpp.LPP_BOUND_ADDITIVE if additive else lpp.LPP_BOUND_MULTIPLICATIVE,
+                                bound_value=lam, rule=lpp.LPP_RULE_SKIP, siblings=lpp.LPP_SIBLINGS_DISTINCT,
+                                uncond_logits=dev(y["target_logits"]), cfg_scale=3.0, top_k=2000)
+    torch.cuda.synchronize()
+    got = {n: t.cpu().numpy() for n, t in out.items()}
+    filt = sampling_frontend(x["target_logits"], y["target_logits"], 3.0, 2000, off, V)
+    rep = compare_verify(parent, dict(x, target_logits=filt), neigh, V, off, k, lam, got, additive=additive,
+                         rule="skip", siblings="without_replacement")
+    print(f"front end + skip + distinct, additive={additive}: {rep}", flush=True)
+    assert rep["nodes"] > 0 and rep["near_tie_decisions"] <= 2
