@@ -22,6 +22,14 @@
 // Barriers wait for LDS traffic only, so global stores stay in flight across
 // them.  Rows with the most children are given the lowest block indices.  The
 // last row of a batch item to finish follows the recorded decisions from the root.
+//
+// Variants of the same kernel (template switches, so that the plain build pays for none of them):
+// FRONT  classifier-free guidance and top-k in front of the target softmax (App. B "Models");
+// ALT    the other reading of two points the paper leaves open: A picked by passing over the
+//        neighbours that would break the bound instead of stopping at the first one (wave 0 walks
+//        the gathered values 64 at a time), and siblings that are distinct draws (a rejected token
+//        leaves p, which is rescaled by 1 / (1 - p(x^))).
+// The additive bound of the earlier LANTERN method is a run-time choice of the cap.
 #include <limits.h>
 #include <math.h>
 
