@@ -374,7 +374,10 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
 #pragma unroll
       for (int d = 0; d < D; ++d) load_full(st[d], min(g + d * KW, hl));
       if (pre) { compute_group(cst, gx, vis, kAny); gx += KW; }   // while the ring's loads are in flight
-      while (g + (D - 1) * KW < h1) {             // whole rounds of the ring
+      // whole rounds of the ring, as long as at least the round's first refill is a group of this
+      // wave (a round that would refill nothing is left to the tail below: a wave with D groups or
+      // fewer would else spend half of the compute unit's load issue on re-reads nobody uses)
+      while (g + D * KW < h1) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
           compute_group(st[d], g, novis, kFull);
@@ -383,7 +386,7 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
         }
       }
 #pragma unroll
-      for (int d = 0; d < D - 1; ++d) {           // what is left: fewer than D groups, already loaded
+      for (int d = 0; d < D; ++d) {               // what is left: up to D groups, already loaded
         if (g < h1) compute_group(st[d], g, novis, kFull);
         g += KW;
       }
