@@ -32,6 +32,7 @@
 // The additive bound of the earlier LANTERN method is a run-time choice of the cap.
 #include <limits.h>
 #include <math.h>
+#include <stdlib.h>
 
 #include <algorithm>
 
@@ -70,6 +71,8 @@ struct VerifyArgs {
   int64_t ldv;
   int32_t off, V, M, B, kstride, k, depth;
   int32_t nstage;         // child lists whose first pass is staged in LDS (<= kMaxStage)
+  int32_t n_parents;      // rows with children (they come first in the row table)
+  int32_t wait_parent, wait_leaf;   // what a row holds its loads back per parent / leaf entry ahead of it (1/256 of 1024 clocks)
   float lambda;           // bound factor, or delta when `additive`
   int32_t additive;       // 0: sum_A r < lambda r(x^)   1: sum_A r < delta
   int32_t skip;           // A: 0 longest nearest-first prefix, 1 neighbours that would break the bound are passed over
@@ -260,7 +263,9 @@ __device__ __forceinline__ float combine_max(const float* s_w, int lane) {
 // FRONT: classifier-free guidance and top-k in front of the target softmax (paper App. B "Models").
 // ALT: the build that also knows the other readings of A and of the sibling scheme
 // (VerifyArgs::skip, ::norepl); the plain build does not carry their registers and LDS.
-template <int NT, int NCH, bool ALIGNED, bool FRONT, bool ALT>
+// STAG: rows hold their logit loads back by their place in the row table (see the kernel body): a
+// build of its own, because the waits force another order of the first loads.
+template <int NT, int NCH, bool ALIGNED, bool FRONT, bool ALT, bool STAG>
 __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab tt) {
   constexpr int NW = NT / 64;
   constexpr int NC = NCH * NW;             // cells
@@ -302,6 +307,36 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   const float* drow = nchild > 0 ? a.drafter + rowoff : nullptr;
   const int nst = min(nchild, a.nstage);
 
+  int crow[kMaxStage], stok[kMaxStage];
+#pragma unroll
+  for (int ci = 0; ci < kMaxStage; ++ci) {
+    crow[ci] = first_child + ci;
+    if (!a.consecutive && ci < nchild) crow[ci] = a.child_idx[cp0 + ci];
+  }
+  if (STAG) {
+    // When the whole grid is resident at once, every row asks for its logits in the same
+    // microsecond and the memory system serves them all at the same pace: the row with the longest
+    // chain of children then starts as late as a leaf.  Here rows with shorter chains hold their
+    // loads back (the host turns the bytes asked for ahead of a row -- the table is sorted by
+    // children, parents first -- into a wait), so that the long chains get theirs first.  The wait
+    // is a sum of fixed sleeps (units of 1024 clocks): no loop stands before the loads.
+    // The drafted tokens, first link of the chain token -> neighbour list, are asked for before the
+    // wait as vector loads at one address for all lanes (unconditional, so that they return in
+    // order ahead of the rows): behind a sleep the compiler no longer makes them scalar loads, and
+    // scalar loads issued before it would have the row loads wait for them.
+    const int e_sorted = blockIdx.x / a.B;
+    const uint32_t wt = (uint32_t)__builtin_amdgcn_readfirstlane(
+        min((min(e_sorted, a.n_parents) * a.wait_parent + max(e_sorted - a.n_parents, 0) * a.wait_leaf) >> 8, 31));
+    int lane_zero = 0;
+    asm("" : "+v"(lane_zero));       // (opaque to the compiler: keeps these loads on the vector path)
+#pragma unroll
+    for (int ci = 0; ci < kMaxStage; ++ci) stok[ci] = a.tokens[nodebase + min(crow[ci], a.M - 1) + lane_zero];
+    if (wt & 1u) __builtin_amdgcn_s_sleep(16);
+    if (wt & 2u) __builtin_amdgcn_s_sleep(32);
+    if (wt & 4u) __builtin_amdgcn_s_sleep(64);
+    if (wt & 8u) { __builtin_amdgcn_s_sleep(64); __builtin_amdgcn_s_sleep(64); }
+    if (wt & 16u) { __builtin_amdgcn_s_sleep(127); __builtin_amdgcn_s_sleep(127); __builtin_amdgcn_s_sleep(2); }
+  }
   // ---- every HBM read of the two rows is issued first: nothing else is as long
   float4 tv[NCH], dv[NCH], uv[FRONT ? NCH : 1];
 #pragma unroll
@@ -320,16 +355,14 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   // ---- the chain row -> drafted tokens -> neighbour lists.  The tokens of the first
   // children sit at wave-uniform addresses (scalar loads, which do not queue behind the rows).
   const float u_fin = a.u_final[nodebase + P];
-  int crow[kMaxStage], stok[kMaxStage];
 #pragma unroll
   for (int ci = 0; ci < kMaxStage; ++ci) {
-    crow[ci] = first_child + ci;
-    if (!a.consecutive && ci < nchild) crow[ci] = a.child_idx[cp0 + ci];
-  }
-#pragma unroll
-  for (int ci = 0; ci < kMaxStage; ++ci) {
-    stok[ci] = 0;
-    if (ci < nchild) stok[ci] = min(max(a.tokens[nodebase + crow[ci]], 0), V - 1);
+    if (STAG) {
+      stok[ci] = ci < nchild ? min(max(__builtin_amdgcn_readfirstlane(stok[ci]), 0), V - 1) : 0;
+    } else {
+      stok[ci] = 0;
+      if (ci < nchild) stok[ci] = min(max(a.tokens[nodebase + crow[ci]], 0), V - 1);
+    }
   }
   int my_tok = 0, my_child = 0;
 #pragma unroll
@@ -903,7 +936,7 @@ __global__ __launch_bounds__(64) void walk_kernel(VerifyArgs a) {
             a.accept_len + b, a.path + (int64_t)b * a.depth, a.final_token + b);
 }
 
-template <int NT, int NCH, bool ALIGNED, bool FRONT, bool ALT>
+template <int NT, int NCH, bool ALIGNED, bool FRONT, bool ALT, bool STAG>
 int32_t launch_rows(const VerifyArgs& a_in, const TreeTab& tt, hipStream_t stream) {
   static size_t attr_lds = 0;   // largest dynamic LDS size this instantiation was enabled for
   VerifyArgs a = a_in;
@@ -914,7 +947,7 @@ int32_t launch_rows(const VerifyArgs& a_in, const TreeTab& tt, hipStream_t strea
   // 160 KB per compute unit, less the kernel's fixed arrays: the widest rows keep fewer lists staged
   while (a.nstage > 0 && lds_for(a.nstage) > 152 * 1024) --a.nstage;
   const size_t lds = lds_for(a.nstage);
-  auto kern = verify_rows_kernel<NT, NCH, ALIGNED, FRONT, ALT>;
+  auto kern = verify_rows_kernel<NT, NCH, ALIGNED, FRONT, ALT, STAG>;
   if (lds > attr_lds) {
     LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -993,6 +1026,24 @@ int32_t relaxed_verify_impl(int32_t additive, int32_t skip, int32_t norepl, bool
     }
     tt.rowinfo[i] = ri;
   }
+  // Stagger (see the kernel): only when every block is resident from the start (one per compute
+  // unit) -- with more blocks than that the launch order, most children first, already does it --
+  // and only for the plain step: with a front end every row has a long stretch of its own before
+  // its chain, which the waits would only push back.
+  a.n_parents = tree->n_parents;
+  a.wait_parent = a.wait_leaf = 0;
+  bool stag = false;
+  if ((int64_t)B * tree->M <= 256 && !front && !alt) {
+    double stagger = 1.0;             // of the time the memory system needs for the bytes asked for ahead of a row
+    if (const char* e = getenv("LPP_VERIFY_STAGGER")) stagger = atof(e);
+    if (!(stagger >= 0.0 && stagger <= 4.0)) stagger = 1.0;
+    // one logit row of every item at 5 TB/s, in 1/256 of the kernel's sleep unit (1024 clocks at 2.4 GHz)
+    const double ticks_per_row = (double)B * V * 4.0 / 5.0e12 * 2.4e9 / 1024.0 * 256.0 * stagger;
+    a.wait_parent = (int32_t)(2.0 * ticks_per_row);
+    a.wait_leaf = (int32_t)ticks_per_row;
+    // worth its other load order only if the last row waits for a few sleep units
+    stag = ((int64_t)tree->n_parents * a.wait_parent + (int64_t)(tree->M - tree->n_parents) * a.wait_leaf) >= 4 * 256;
+  }
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   auto aligned16 = [&](const float* p) {
@@ -1001,11 +1052,13 @@ int32_t relaxed_verify_impl(int32_t additive, int32_t skip, int32_t norepl, bool
   const bool al = aligned16(target_logits) && aligned16(drafter_logits) && aligned16(uncond_logits);
   int32_t st;
 #define LPP_DISPATCH2(T, N, ALT)                                                                            \
-  st = front ? (al ? launch_rows<T, N, true, true, ALT>(a, tt, s) : launch_rows<T, N, false, true, ALT>(a, tt, s))   \
-             : (al ? launch_rows<T, N, true, false, ALT>(a, tt, s) : launch_rows<T, N, false, false, ALT>(a, tt, s))
+  st = front ? (al ? launch_rows<T, N, true, true, ALT, false>(a, tt, s) : launch_rows<T, N, false, true, ALT, false>(a, tt, s))   \
+             : (al ? launch_rows<T, N, true, false, ALT, false>(a, tt, s) : launch_rows<T, N, false, false, ALT, false>(a, tt, s))
 #define LPP_DISPATCH(T, N)                                     \
   do {                                                         \
-    if (alt) { LPP_DISPATCH2(T, N, true); } else { LPP_DISPATCH2(T, N, false); } \
+    if (stag) {                                                \
+      st = al ? launch_rows<T, N, true, false, false, true>(a, tt, s) : launch_rows<T, N, false, false, false, true>(a, tt, s); \
+    } else if (alt) { LPP_DISPATCH2(T, N, true); } else { LPP_DISPATCH2(T, N, false); } \
   } while (0)
   if (V <= 2048) LPP_DISPATCH(512, 1);
   else if (V <= 4096) LPP_DISPATCH(512, 2);
