@@ -115,6 +115,23 @@ __device__ __forceinline__ float wave_inclusive_scan(float v) {
   v += dpp_or<0x143, 0xc>(0.f, v);   // row_bcast:31 into rows 2 and 3
   return v;
 }
+// N scans side by side, step by step: the steps of one scan depend on each other, those of
+// different scans do not, so their latencies overlap.
+template <int N>
+__device__ __forceinline__ void wave_inclusive_scan_n(float (&v)[N]) {
+#pragma unroll
+  for (int j = 0; j < N; ++j) v[j] += dpp_or<0x111, 0xf>(0.f, v[j]);
+#pragma unroll
+  for (int j = 0; j < N; ++j) v[j] += dpp_or<0x112, 0xf>(0.f, v[j]);
+#pragma unroll
+  for (int j = 0; j < N; ++j) v[j] += dpp_or<0x114, 0xf>(0.f, v[j]);
+#pragma unroll
+  for (int j = 0; j < N; ++j) v[j] += dpp_or<0x118, 0xf>(0.f, v[j]);
+#pragma unroll
+  for (int j = 0; j < N; ++j) v[j] += dpp_or<0x142, 0xa>(0.f, v[j]);
+#pragma unroll
+  for (int j = 0; j < N; ++j) v[j] += dpp_or<0x143, 0xc>(0.f, v[j]);
+}
 // Inclusive scan of non-negative values that is non-decreasing over the lanes.
 // The tree above adds in a different order per lane, so neighbouring results can
 // be out of order by a rounding; a running maximum puts them back in order.
@@ -625,22 +642,61 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
 #pragma unroll
     for (int e = 0; e < 4; ++e) p_reg[j][e] = p_reg[j][e] * inv_sd;
 
-  if (P == 0 && tid == 0) {  // row 0 is no drafted node: defined outputs
-    __hip_atomic_store(&a.ws_decision[nodebase], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (a.decision) a.decision[nodebase] = 0;
-    if (a.ratio) a.ratio[nodebase] = 0.f;
-    if (a.mass) a.mass[nodebase] = 0.f;
-    if (a.n_agg) a.n_agg[nodebase] = 0;
-    if (a.q_tok) a.q_tok[nodebase] = 0.f;
-    if (a.p_tok) a.p_tok[nodebase] = 0.f;
-  }
-
   // ---- children in static order, each against the current residual r
   int tog = 0;
   float pscale = 1.f;        // ALT, distinct siblings: p = p_reg * pscale once rejected tokens have left p
+  // What a child's test leaves behind is kept by lane `ci` of the block and written out for up to
+  // 64 children at once when the loop is over (by wave 0 after the draw; waves that own children
+  // 64 and up, before they leave): the per-child chain below then carries no global stores.
+  float k_m = 0.f, k_qt = 0.f, k_pt = 0.f;
+  int k_j = 0;
+  auto write_children = [&](int first, int count) {
+    if (lane < count) {
+      const int cc = first + lane;
+      const int c = s_child[cc];
+      const float pt = ALT ? k_pt : exp2_fma(s_dlog[cc], md2) * inv_sd;   // p(x^): the drafter's probability of the token
+      const int dec = (s_u[cc] * pt < k_m) ? 1 : 0;                        // u < min(1, mass / p(x^))
+      // what the walk needs of this node: a device-scope store, visible to every compute unit
+      // once it has completed (no cache write-back needed before the ticket below)
+      __hip_atomic_store(&a.ws_decision[nodebase + c], (P << 1) | dec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
+      if (a.ratio) a.ratio[nodebase + c] = k_m / pt;
+      if (a.mass) a.mass[nodebase + c] = k_m;
+      if (a.n_agg) a.n_agg[nodebase + c] = k_j;
+      if (a.q_tok) a.q_tok[nodebase + c] = k_qt;
+      if (a.p_tok) a.p_tok[nodebase + c] = pt;
+    }
+  };
+  // Token and first-pass operands of the child about to be taken.  They are fetched ahead of its
+  // turn: token and slot indices while the previous child's residual is formed, the values of r
+  // right behind the barrier that ends it and before that residual's sum is known (r is read
+  // again in the rare case that the sum turns out empty and r is put back).
+  auto first_slots = [&](int cj, int tj) -> uint32_t {
+    if (cj < nst) return s_neigh[cj * NT + tid];
+    const int32_t* nrow = a.neigh + (int64_t)tj * a.kstride;
+    const int sl0 = 2 * tid;
+    const int x0 = nrow[min(sl0, k - 1)], x1 = nrow[min(sl0 + 1, k - 1)];
+    int n0 = min(max(x0, 0), V - 1), n1 = min(max(x1, 0), V - 1);
+    if (sl0 == 0) n0 = tj;
+    if (sl0 >= k) n0 = ZC;
+    if (sl0 + 1 >= k) n1 = ZC;
+    return (uint32_t)n0 | ((uint32_t)n1 << 16);
+  };
+  int t_nx = 0;
+  uint32_t pk_nx = (uint32_t)ZC | ((uint32_t)ZC << 16);
+  float rt_nx = 0.f, v0_nx = 0.f, v1_nx = 0.f;
+  if (nchild > 0) {
+    t_nx = s_tok[0];
+    pk_nx = first_slots(0, t_nx);
+    rt_nx = r_lds[t_nx];
+    v0_nx = r_lds[pk_nx & 0xFFFFu];
+    v1_nx = r_lds[pk_nx >> 16];
+  }
   for (int ci = 0; ci < nchild; ++ci) {
-    const int t = s_tok[ci];
-    const float rt = r_lds[t];
+    const int t = t_nx;
+    const float rt = rt_nx;
+    const uint32_t pk_first = pk_nx;
+    const float v0_first = v0_nx, v1_first = v1_nx;
     const bool skip_rule = ALT && a.skip;
     float cum_sk = rt;       // (wave 0) mass of A so far under the skip rule: x^ is always a member
     int cnt_sk = 0;          // (wave 0) members besides x^
@@ -664,18 +720,17 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       if (ps * PASS < k && !found) {                 // uniform
         const int sl0 = ps * PASS + 2 * tid;
         uint32_t pk;
-        if (ps == 0 && ci < nst) {
-          pk = s_neigh[ci * NT + tid];
+        if (ps == 0) {
+          pk = pk_first;
         } else {
           const int x0 = nrow[min(sl0, k - 1)], x1 = nrow[min(sl0 + 1, k - 1)];
           int n0 = min(max(x0, 0), V - 1), n1 = min(max(x1, 0), V - 1);
-          if (sl0 == 0) n0 = t;
           if (sl0 >= k) n0 = ZC;
           if (sl0 + 1 >= k) n1 = ZC;
           pk = (uint32_t)n0 | ((uint32_t)n1 << 16);
         }
         const int n0 = pk & 0xFFFFu, n1 = pk >> 16;
-        const float v0 = r_lds[n0], v1 = r_lds[n1];
+        const float v0 = ps == 0 ? v0_first : r_lds[n0], v1 = ps == 0 ? v1_first : r_lds[n1];
         bool z0, z1;
         if (skip_rule) {
           // Neighbours are visited nearest first; one whose value would lift the sum to the cap is
@@ -748,33 +803,25 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     if (ci < 8) LPP_TS(4 + 3 * ci);
     lds_barrier();
     if (ci < 8) LPP_TS(5 + 3 * ci);
-    // p(x^): the drafter's probability of the token; with distinct siblings, of what is left of p
+    // p(x^) with distinct siblings: the drafter's probability of the token in what is left of p
     float pt = 0.f;
-    if (ALT || tid == 0) pt = exp2_fma(s_dlog[ci], md2) * inv_sd;
-    if (ALT && a.norepl) {
-      pt = pt * pscale;
-      for (int cj = 0; cj < ci; ++cj)
-        if (s_tok[cj] == t) pt = 0.f;                           // already tried: it has left p
-    }
-    if (tid == 0) {
-      const int c = s_child[ci];
-      const int jstar = s_jstar;
-      const float qt = rt * rs, m = s_mass * rs;
-      const int dec = (s_u[ci] * pt < m) ? 1 : 0;               // u < min(1, mass / p(x^))
-      // what the walk needs of this node: a device-scope store, visible to every compute unit
-      // once it has completed (no cache write-back needed before the ticket below)
-      __hip_atomic_store(&a.ws_decision[nodebase + c], (P << 1) | dec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
-      if (a.ratio) a.ratio[nodebase + c] = m / pt;
-      if (a.mass) a.mass[nodebase + c] = m;
-      if (a.n_agg) a.n_agg[nodebase + c] = jstar;
-      if (a.q_tok) a.q_tok[nodebase + c] = qt;
-      if (a.p_tok) a.p_tok[nodebase + c] = pt;
+    if (ALT) {
+      pt = exp2_fma(s_dlog[ci], md2) * inv_sd;
+      if (a.norepl) {
+        pt = pt * pscale;
+        for (int cj = 0; cj < ci; ++cj)
+          if (s_tok[cj] == t) pt = 0.f;                         // already tried: it has left p
+      }
     }
     // outcome "rejected": keep the positive part of (r' - p); its sum is the new normaliser
     // (Eq. 2).  Product and difference are rounded separately: a drafter equal to the target
     // then leaves exactly nothing.  (r' rs - p <= 1, so clamping to [0, 1] is the positive part:
     // it folds into the subtraction.)
+    {
+      const int cn = min(ci + 1, nchild - 1);                   // (after the last child: its own, unused)
+      t_nx = s_tok[cn];
+      pk_nx = first_slots(cn, t_nx);
+    }
     float4 rv[NCH];
     float z = 0.f;
 #pragma unroll
@@ -796,11 +843,19 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       z += (res.x + res.y) + (res.z + res.w);
       *own = res;
     }
+    if (w == (ci >> 6)) {
+      const float m = s_mass * rs;
+      const int jstar = s_jstar;
+      if (tid == ci) { k_m = m; k_j = jstar; k_qt = rt * rs; k_pt = pt; }
+    }
     z = wave_sum(z);
     if (lane == 0) s_z[ci & 1][w] = z;
     lds_barrier();
     if (ci < 8) LPP_TS(6 + 3 * ci);
     z = combine_sum<NW>(s_z[ci & 1], lane);
+    rt_nx = r_lds[t_nx];
+    v0_nx = r_lds[pk_nx & 0xFFFFu];
+    v1_nx = r_lds[pk_nx >> 16];
     if (z > 0.f) {
       rs = 1.0f / z;
     } else {
@@ -816,6 +871,9 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       }
       if (tid == 0) r_lds[t] = rt;
       lds_barrier();
+      rt_nx = r_lds[t_nx];
+      v0_nx = r_lds[pk_nx & 0xFFFFu];
+      v1_nx = r_lds[pk_nx >> 16];
     }
     if (ALT && a.norepl) {
       // the rejected token leaves p; the rest is divided by what it leaves behind
@@ -831,14 +889,33 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
 
   // ---- draw from the final r by inverse CDF over ascending token index: cell sums by
   // their owners, then wave 0 finds the cell, the lane and the token.
+  {
+    // (all reads first, then the NCH reductions side by side: their steps are independent)
+    float cs[NCH];
 #pragma unroll
-  for (int j = 0; j < NCH; ++j) {
-    const float4 rv = *reinterpret_cast<const float4*>(&r_lds[4 * (tid + NT * j)]);
-    const float tot = wave_sum((rv.x + rv.y) + (rv.z + rv.w));
-    if (lane == 0) s_cell[j * NW + w] = tot;
+    for (int j = 0; j < NCH; ++j) {
+      const float4 cv = *reinterpret_cast<const float4*>(&r_lds[4 * (tid + NT * j)]);
+      cs[j] = (cv.x + cv.y) + (cv.z + cv.w);
+    }
+    wave_inclusive_scan_n<NCH>(cs);
+    float mine = 0.f;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const float tot = lane_value(cs[j], 63);
+      if (lane == j) mine = tot;
+    }
+    if (lane < NCH) s_cell[lane * NW + w] = mine;
   }
   for (int i = NC + tid; i < 64 * CPL; i += NT) s_cell[i] = 0.f;
   LPP_TS(28);
+  if (w != 0 && nchild > 64 * w) {
+    // (rare: more than 64 children)  this wave's stores have to be complete before wave 0 takes
+    // the row's ticket, which it does after the barrier below
+    write_children(64 * w, min(nchild - 64 * w, 64));
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+  }
   lds_barrier();
   if (w != 0) return;
 
@@ -902,12 +979,22 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   }
   x = min(x, V - 1);
   LPP_TS(29);
+  write_children(0, min(nchild, 64));
   int ticket = 0;
   if (lane == 0) {
+    if (P == 0) {  // row 0 is no drafted node: defined outputs
+      __hip_atomic_store(&a.ws_decision[nodebase], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (a.decision) a.decision[nodebase] = 0;
+      if (a.ratio) a.ratio[nodebase] = 0.f;
+      if (a.mass) a.mass[nodebase] = 0.f;
+      if (a.n_agg) a.n_agg[nodebase] = 0;
+      if (a.q_tok) a.q_tok[nodebase] = 0.f;
+      if (a.p_tok) a.p_tok[nodebase] = 0.f;
+    }
     __hip_atomic_store(&a.ws_final[nodebase + P], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (a.final_all) a.final_all[nodebase + P] = x;
     if (a.counters) {
-      // every store of this row's decisions and draw was issued by this lane: once they have
+      // every store of this row's decisions and draw was issued by this wave: once they have
       // completed they are visible device-wide, and only then the ticket is taken
       __atomic_signal_fence(__ATOMIC_SEQ_CST);
       __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
