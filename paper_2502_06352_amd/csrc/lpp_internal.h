@@ -27,6 +27,10 @@ struct lpp_tree {
   // "last block done" tickets of the fused kernels: zero between calls.  Calls that
   // share one handle must therefore be ordered on a stream.
   int32_t* d_counters = nullptr;   // [2 * LPP_COUNTER_SLOTS]: verify, then attention
+  // verify with the whole grid resident: words the rows leave for the block that walks
+  // ([LPP_MAX_ROWS] decisions, [LPP_MAX_ROWS] draws: -1 between calls; then one word that is
+  // raised for good when a walk gave up)
+  int32_t* d_mail = nullptr;       // [2 * LPP_MAX_ROWS + 1]
 };
 
 #define LPP_COUNTER_SLOTS 4096

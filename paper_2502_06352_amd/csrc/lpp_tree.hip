@@ -82,6 +82,10 @@ extern "C" int32_t lpp_tree_create(const int32_t* parent_host, int32_t M, lpp_tr
   const size_t b_cnt = sizeof(int32_t) * 2 * LPP_COUNTER_SLOTS;
   if (hipMalloc((void**)&t->d_counters, b_cnt) != hipSuccess) return fail();
   if (hipMemset(t->d_counters, 0, b_cnt) != hipSuccess) return fail();
+  const size_t b_mail = sizeof(int32_t) * 2 * LPP_MAX_ROWS;
+  if (hipMalloc((void**)&t->d_mail, b_mail + sizeof(int32_t)) != hipSuccess) return fail();
+  if (hipMemset(t->d_mail, 0xFF, b_mail) != hipSuccess) return fail();
+  if (hipMemset(t->d_mail + 2 * LPP_MAX_ROWS, 0, sizeof(int32_t)) != hipSuccess) return fail();
   if (hipMemcpy(t->d_child_ptr, t->child_ptr.data(), b_ptr, hipMemcpyHostToDevice) != hipSuccess) return fail();
   if (hipMemcpy(t->d_child_idx, t->child_idx.data(), b_idx, hipMemcpyHostToDevice) != hipSuccess) return fail();
   if (hipMemcpy(t->d_anc, t->anc.data(), b_anc, hipMemcpyHostToDevice) != hipSuccess) return fail();
@@ -95,6 +99,7 @@ extern "C" int32_t lpp_tree_destroy(lpp_tree* t) {
   if (t->d_child_idx) (void)hipFree(t->d_child_idx);
   if (t->d_anc) (void)hipFree(t->d_anc);
   if (t->d_counters) (void)hipFree(t->d_counters);
+  if (t->d_mail) (void)hipFree(t->d_mail);
   delete t;
   return LPP_OK;
 }

@@ -94,6 +94,7 @@ struct VerifyArgs {
   int32_t* ws_decision;   // [B*M] always written: the walk reads these
   int32_t* ws_final;      // [B*M]
   int32_t* counters;      // [B] zero between calls, or null: walk runs as its own kernel
+  int32_t spin_limit;     // (whole grid resident) how often the walking block asks for the other rows' words
   const int32_t* child_idx;   // [N] children of all rows, grouped by parent (read only if !consecutive)
   int32_t consecutive;    // every row's children are consecutive rows
 #ifdef LPP_VERIFY_TIMESTAMPS
@@ -251,6 +252,108 @@ __device__ __forceinline__ void walk_wave(const int32_t* word, const int32_t* fi
   }
 }
 
+// Walk of one item when the whole grid is resident at once (one wave of the block that walks).
+// Every other row of the item leaves its words -- (parent << 1 | decision) per child, its draw --
+// in `mail` (device-scope stores; -1 = not there yet), this wave asks for them until none is
+// missing, puts -1 back for the next call and walks as above.  Nobody waits for this block, so
+// the wait ends as soon as the other blocks have run; it is bounded all the same (`spin_limit`
+// rounds of loads): when the bound is hit the item's accept_len, path and final token are set
+// to -1 and mail[2 * LPP_MAX_ROWS] is raised, which makes every later call on this tree fail
+// the same way (words may arrive after this call gave up: the mail is no longer clean).
+// s_own: [M] words of this block's own children, -1 elsewhere; s_next, s_fin: M ints each;
+// *s_end: row the path ended on (-1: failed), for the wave that holds this block's own draw.
+// The first round of loads is issued by the caller ahead of time (mail_fetch), so that it is in
+// flight while this wave still has other work.
+struct MailRound {
+  int w[LPP_MAX_ROWS / 64], f[LPP_MAX_ROWS / 64];
+  int gave_up;
+};
+__device__ __forceinline__ void mail_fetch(MailRound& r, const int32_t* mail, int64_t nodebase, int M, int lane) {
+#pragma unroll
+  for (int q = 0; q < LPP_MAX_ROWS / 64; ++q) {       // all loads of a round in flight together
+    const int ic = min(lane + 64 * q, M - 1);
+    r.w[q] = __hip_atomic_load(&mail[nodebase + ic], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    r.f[q] = __hip_atomic_load(&mail[LPP_MAX_ROWS + nodebase + ic], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  r.gave_up = __hip_atomic_load(&mail[2 * LPP_MAX_ROWS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void collect_and_walk(MailRound r, int32_t* mail, int64_t nodebase, int M, int depth,
+                                                 int P, int spin_limit, int lane, const int* s_own, int* s_next,
+                                                 int* s_fin, int* s_end, int32_t* accept_len, int32_t* path,
+                                                 int32_t* final_token) {
+  constexpr int Q = LPP_MAX_ROWS / 64;
+  int32_t* md = mail + nodebase;
+  int32_t* mf = mail + LPP_MAX_ROWS + nodebase;
+  int wd[Q], fn[Q];
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int i = lane + 64 * q;
+    wd[q] = (i >= 1 && i < M) ? s_own[i] : 0;
+    fn[q] = (i < M && i != P) ? -1 : 0;
+  }
+  bool ok = false;
+  // (a negative limit makes the walk give up at once: the host's way to exercise that path)
+  if (r.gave_up == 0 && spin_limit >= 0) {
+    for (int spin = 0;; ++spin) {
+      bool missing = false;
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+        if (wd[q] == -1) wd[q] = r.w[q];
+        if (fn[q] == -1) fn[q] = r.f[q];
+        missing = missing || wd[q] == -1 || fn[q] == -1;
+      }
+      if (!__ballot(missing)) { ok = true; break; }
+      if (spin >= spin_limit) break;
+      __builtin_amdgcn_s_sleep(4);
+      mail_fetch(r, mail, nodebase, M, lane);
+    }
+  }
+  if (!ok) {
+    if (lane == 0) {
+      __hip_atomic_store(&mail[2 * LPP_MAX_ROWS], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int i = 0; i < depth; ++i) path[i] = -1;
+      *accept_len = -1;
+      *final_token = -1;
+      *s_end = -1;
+    }
+    return;
+  }
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int i = lane + 64 * q;
+    if (i < M) {
+      __hip_atomic_store(&md[i], -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // ready for the next call
+      __hip_atomic_store(&mf[i], -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_fin[i] = fn[q];
+      s_next[i] = INT_MAX;
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int i = lane + 64 * q;
+    if (i >= 1 && i < M && (wd[q] & 1)) atomicMin(&s_next[wd[q] >> 1], i);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+  if (lane == 0) {
+    int cur = 0, n = 0;
+    while (n < depth) {
+      const int nxt = s_next[cur];
+      if (nxt == INT_MAX) break;
+      path[n++] = nxt;
+      cur = nxt;
+    }
+    for (int i = n; i < depth; ++i) path[i] = -1;
+    *accept_len = n;
+    if (cur != P) *final_token = s_fin[cur];      // (ended on this block's own row: its draw is with wave 0)
+    *s_end = cur;
+  }
+}
+
 // Sum (max), in wave order, of one float per wave held in LDS; every wave
 // computes the same value the same way.
 template <int NW>
@@ -308,6 +411,8 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   __shared__ int s_ncand;
   __shared__ uint32_t s_tau;
   __shared__ float s_mass;
+  // (whole grid resident) the walking block: words of its own children, next[], finals, end of the path
+  __shared__ int s_mail[STAG ? 3 * LPP_MAX_ROWS + 1 : 1];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -323,6 +428,11 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   const int first_child = (ri >> 16) & 255u, cp0 = ri >> 24;
   const float* drow = nchild > 0 ? a.drafter + rowoff : nullptr;
   const int nst = min(nchild, a.nstage);
+  // When the whole grid is resident at once there are no tickets: the block of the first table
+  // entry (most children, as a rule the last to finish) collects the other rows' words itself,
+  // in a wave of its own beside the draw, and walks.  The other rows never wait for anybody.
+  const bool walker = STAG && blockIdx.x < (unsigned)a.B;
+  if (STAG && walker && tid < a.M) s_mail[tid] = -1;        // (read after several barriers)
 
   int crow[kMaxStage], stok[kMaxStage];
 #pragma unroll
@@ -658,7 +768,8 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       const int dec = (s_u[cc] * pt < k_m) ? 1 : 0;                        // u < min(1, mass / p(x^))
       // what the walk needs of this node: a device-scope store, visible to every compute unit
       // once it has completed (no cache write-back needed before the ticket below)
-      __hip_atomic_store(&a.ws_decision[nodebase + c], (P << 1) | dec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (!(STAG && walker))
+        __hip_atomic_store(&a.ws_decision[nodebase + c], (P << 1) | dec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
       if (a.ratio) a.ratio[nodebase + c] = k_m / pt;
       if (a.mass) a.mass[nodebase + c] = k_m;
@@ -887,6 +998,8 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     }
   }
 
+  MailRound mail_first;      // (the wave that walks) asked for now, looked at after the cell sums
+  if (STAG && walker && w == 1) mail_fetch(mail_first, a.ws_decision, nodebase, a.M, lane);
   // ---- draw from the final r by inverse CDF over ascending token index: cell sums by
   // their owners, then wave 0 finds the cell, the lane and the token.
   {
@@ -916,8 +1029,21 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
   }
+  if (STAG && walker && tid < nchild) {
+    // the walking block's own children: their words go to the wave that walks through LDS
+    const float pt = ALT ? k_pt : exp2_fma(s_dlog[tid], md2) * inv_sd;
+    s_mail[s_child[tid]] = (P << 1) | ((s_u[tid] * pt < k_m) ? 1 : 0);
+  }
   lds_barrier();
-  if (w != 0) return;
+  if (w != 0) {
+    if (!(STAG && walker)) return;
+    if (w == 1)
+      collect_and_walk(mail_first, a.ws_decision, nodebase, a.M, a.depth, P, a.spin_limit, lane, s_mail, s_mail + LPP_MAX_ROWS,
+                       s_mail + 2 * LPP_MAX_ROWS, s_mail + 3 * LPP_MAX_ROWS, a.accept_len + b,
+                       a.path + (int64_t)b * a.depth, a.final_token + b);
+    lds_barrier();           // (met by wave 0 once it holds the draw)
+    return;
+  }
 
   float cpre[CPL];           // running sum over my cells
   {
@@ -983,7 +1109,7 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   int ticket = 0;
   if (lane == 0) {
     if (P == 0) {  // row 0 is no drafted node: defined outputs
-      __hip_atomic_store(&a.ws_decision[nodebase], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (!STAG) __hip_atomic_store(&a.ws_decision[nodebase], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (a.decision) a.decision[nodebase] = 0;
       if (a.ratio) a.ratio[nodebase] = 0.f;
       if (a.mass) a.mass[nodebase] = 0.f;
@@ -991,9 +1117,10 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       if (a.q_tok) a.q_tok[nodebase] = 0.f;
       if (a.p_tok) a.p_tok[nodebase] = 0.f;
     }
-    __hip_atomic_store(&a.ws_final[nodebase + P], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!(STAG && walker))
+      __hip_atomic_store(&a.ws_final[nodebase + P], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (a.final_all) a.final_all[nodebase + P] = x;
-    if (a.counters) {
+    if (!STAG && a.counters) {
       // every store of this row's decisions and draw was issued by this wave: once they have
       // completed they are visible device-wide, and only then the ticket is taken
       __atomic_signal_fence(__ATOMIC_SEQ_CST);
@@ -1001,6 +1128,14 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
       __atomic_signal_fence(__ATOMIC_SEQ_CST);
       ticket = __hip_atomic_fetch_add(&a.counters[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+  }
+  if (STAG) {
+    if (walker) {
+      lds_barrier();         // the walk is done
+      if (lane == 0 && s_mail[3 * LPP_MAX_ROWS] == P) a.final_token[b] = x;
+      LPP_TS(30);
+    }
+    return;
   }
   if (!a.counters) return;
   ticket = __builtin_amdgcn_readfirstlane(ticket);
@@ -1094,8 +1229,9 @@ int32_t relaxed_verify_impl(int32_t additive, int32_t skip, int32_t norepl, bool
   a.ws_decision = reinterpret_cast<int32_t*>(ws);
   a.ws_final = reinterpret_cast<int32_t*>(reinterpret_cast<unsigned char*>(ws) +
                                           lpp_align_up(nodes * sizeof(int32_t), 256));
-  const bool fused_walk = B <= LPP_COUNTER_SLOTS;
+  bool fused_walk = B <= LPP_COUNTER_SLOTS;
   a.counters = fused_walk ? tree->d_counters : nullptr;
+  a.spin_limit = 0;
 #ifdef LPP_VERIFY_TIMESTAMPS
   a.ts = reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(ws) + need);
 #endif
@@ -1113,14 +1249,22 @@ int32_t relaxed_verify_impl(int32_t additive, int32_t skip, int32_t norepl, bool
     }
     tt.rowinfo[i] = ri;
   }
-  // Stagger (see the kernel): only when every block is resident from the start (one per compute
-  // unit) -- with more blocks than that the launch order, most children first, already does it --
-  // and only for the plain step: with a front end every row has a long stretch of its own before
-  // its chain, which the waits would only push back.
+  // Whole grid resident at once (one block per compute unit, the plain step only): rows hold their
+  // loads back by chain length and the walk needs no tickets (see the kernel).  With more blocks
+  // than compute units the launch order, most children first, already staggers the rows; with a
+  // front end every row has a long stretch of its own before its chain, which waits would only
+  // push back.
   a.n_parents = tree->n_parents;
   a.wait_parent = a.wait_leaf = 0;
-  bool stag = false;
-  if ((int64_t)B * tree->M <= 256 && !front && !alt) {
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    LPP_HIP_TRY(hipGetDevice(&dev));
+    LPP_HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+    n_cu = std::max(v, 1);
+  }
+  const bool stag = (int64_t)B * tree->M <= std::min(n_cu, LPP_MAX_ROWS) && !front && !alt && tree->d_mail != nullptr;
+  if (stag) {
     double stagger = 1.0;             // of the time the memory system needs for the bytes asked for ahead of a row
     if (const char* e = getenv("LPP_VERIFY_STAGGER")) stagger = atof(e);
     if (!(stagger >= 0.0 && stagger <= 4.0)) stagger = 1.0;
@@ -1128,8 +1272,14 @@ int32_t relaxed_verify_impl(int32_t additive, int32_t skip, int32_t norepl, bool
     const double ticks_per_row = (double)B * V * 4.0 / 5.0e12 * 2.4e9 / 1024.0 * 256.0 * stagger;
     a.wait_parent = (int32_t)(2.0 * ticks_per_row);
     a.wait_leaf = (int32_t)ticks_per_row;
-    // worth its other load order only if the last row waits for a few sleep units
-    stag = ((int64_t)tree->n_parents * a.wait_parent + (int64_t)(tree->M - tree->n_parents) * a.wait_leaf) >= 4 * 256;
+    // the other rows' words reach the walking block through the tree's mail words, not the workspace
+    a.ws_decision = tree->d_mail;
+    a.ws_final = tree->d_mail + LPP_MAX_ROWS;
+    a.counters = nullptr;
+    fused_walk = true;
+    // about 0.5 us a round: a quarter of a second before the walk gives up (see collect_and_walk)
+    a.spin_limit = 1 << 19;
+    if (const char* e = getenv("LPP_VERIFY_SPIN_LIMIT")) a.spin_limit = std::max(-1, std::min(atoi(e), 1 << 19));
   }
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
