@@ -157,6 +157,14 @@ int32_t lpp_tree_attention_gqa(const lpp_tree* tree, int32_t dtype, int32_t out_
  * Errors: LPP_EINVAL (null, B < 1, V < 1, k < 1, k > kstride, k > V,
  * vocab_offset < 0, vocab_offset + V > ldv, lambda NaN), LPP_EUNSUPPORTED
  * (V > LPP_MAX_VOCAB, k > LPP_MAX_K), LPP_ENOWORKSPACE, LPP_EHIP.
+ * The calls keep a few words of state in the tree handle between kernels (tickets, the rows'
+ * results on their way to the block that walks): calls that share a handle must be ordered on
+ * a stream.  When B * M blocks fit the device at once, the walk of an item is done by one of
+ * its row blocks, which waits for the others' results; that wait is bounded, and nobody waits
+ * for that block.  Should it ever run out (it cannot unless the other blocks of the launch do
+ * not run), accept_len[b], path[b, :] and final_token[b] are set to -1, and so are those of
+ * every later call with this handle: make a new one.  LPP_VERIFY_SPIN_LIMIT=-1 in the
+ * environment forces that outcome (for tests of the caller's handling).
  */
 typedef struct lpp_verify_out {
   int32_t* accept_len;     /* [device] [B]        number of accepted drafted nodes            */

@@ -129,3 +129,39 @@ def test_verify_argument_errors_on_device():
     with pytest.raises(lpp.LppError) as e:
         run_verify(tree, x, neigh, cfg.V, 8, cfg.ldv, 4, 2.0)       # slice leaves the row
     assert e.value.status == lpp.LPP_EINVAL
+
+
+def test_verify_walk_by_a_row_other_than_the_root_and_repeated_calls():
+    # The row with the most children is not row 0 here: with the whole grid resident its block is
+    # the one that collects the other rows' results and walks.  Several calls on one handle, with
+    # different inputs, each against the oracle: what a call leaves behind must not reach the next.
+    cfg = CONFIGS[1]
+    parent = np.array([-1, 0, 1, 1, 1, 1, 0, 6, 2, 2], dtype=np.int32)
+    tree = lpp.Tree(parent)
+    E = make_codebook(cfg)
+    for salt, rho in ((0, 0.0), (1, 0.8), (2, 0.5), (3, 1.0)):
+        x = make_verify_inputs(cfg, parent, rho=rho, salt=salt)
+        neigh = sparse_neighbour_table(E, cfg.k, x["tokens"][:, 1:], cfg.V)
+        got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam)
+        rep = compare_verify(parent, x, neigh, cfg.V, cfg.vocab_offset, cfg.k, cfg.lam, got)
+        assert rep["nodes"] > 0
+
+
+def test_verify_walk_that_gives_up_is_loud(monkeypatch):
+    # The bounded wait of the walking block is made to run out from the host (no kernel hangs or
+    # faults: the block just does not look at the results).  The call must say so in its outputs,
+    # the handle must stay marked, and a new handle must work.
+    cfg = CONFIGS[1]
+    parent = static_tree(cfg.branching, cfg.N)
+    x = make_verify_inputs(cfg, parent, rho=0.8)
+    neigh = sparse_neighbour_table(make_codebook(cfg), cfg.k, x["tokens"][:, 1:], cfg.V)
+    tree = lpp.Tree(parent)
+    monkeypatch.setenv("LPP_VERIFY_SPIN_LIMIT", "-1")
+    got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam, want_all=False)
+    assert np.all(got["accept_len"] == -1) and np.all(got["final_token"] == -1) and np.all(got["path"] == -1)
+    monkeypatch.delenv("LPP_VERIFY_SPIN_LIMIT")
+    got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam, want_all=False)
+    assert np.all(got["accept_len"] == -1) and np.all(got["final_token"] == -1)
+    fresh = lpp.Tree(parent)
+    got = run_verify(fresh, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam)
+    compare_verify(parent, x, neigh, cfg.V, cfg.vocab_offset, cfg.k, cfg.lam, got)
