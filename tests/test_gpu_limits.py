@@ -48,6 +48,26 @@ def test_verify_most_rows_and_a_row_with_many_children():
     _verify_case(cfg, opts=opts, rule="skip", siblings="without_replacement")
 
 
+@pytest.mark.parametrize("B", [1, 3])
+def test_verify_row_with_more_children_than_a_wave_has_lanes(B):
+    # 100 children of the root, two more below the first of them: the per-child results of such
+    # a row are kept and written out by more than one wave.  B = 1: the whole grid is resident
+    # (103 blocks; the root's block walks, its second wave owning children 64..99 as well);
+    # B = 3: more blocks than compute units, the walk by tickets.
+    cfg = CONFIGS[1].scaled(V=1024, ldv=1024, k=16, B=B)
+    parent = np.array([-1] + [0] * 100 + [1, 1], dtype=np.int32)
+    x = make_verify_inputs(cfg, parent, rho=0.3)
+    neigh = sparse_neighbour_table(make_codebook(cfg), cfg.k, x["tokens"][:, 1:], cfg.V)
+    tree = lpp.Tree(parent)
+    got = run_verify(tree, x, neigh, cfg.V, 0, cfg.ldv, cfg.k, cfg.lam)
+    rep = compare_verify(parent, x, neigh, cfg.V, 0, cfg.k, cfg.lam, got)
+    print(f"100 children, B={B}: {rep}", flush=True)
+    assert rep["nodes"] + rep["skipped_after_tie"] == B * 102
+    opts = dict(rule=lpp.LPP_RULE_SKIP, siblings=lpp.LPP_SIBLINGS_DISTINCT)
+    got = run_verify(tree, x, neigh, cfg.V, 0, cfg.ldv, cfg.k, cfg.lam, opts=opts)
+    compare_verify(parent, x, neigh, cfg.V, 0, cfg.k, cfg.lam, got, rule="skip", siblings="without_replacement")
+
+
 def test_verify_more_items_than_walk_counters():
     cfg = CONFIGS[1].scaled(V=64, ldv=64, k=4, N=3, branching=(2, 1), B=4100)
     rep = _verify_case(cfg, rho=0.9)
