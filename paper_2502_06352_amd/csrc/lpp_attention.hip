@@ -405,10 +405,11 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
 #ifdef LPP_ATTN_TIMESTAMPS
   if (lane == 0) a.ts[(int64_t)blockIdx.x * 16 + 8 + wave] = __builtin_amdgcn_s_memrealtime();
 #endif
-  __syncthreads();   // every wave is done with its V tiles: the buffer is reused below
-  LPP_ATS(2);
+  // (the maxima and sums have a place of their own behind the V tiles, so a wave can leave them
+  // there as soon as it is done; O is parked over the V tiles once every wave is done with them)
+  constexpr int OBYTES = MS * ROWS * OPITCH * 4, VBYTES = KW * 2 * VTILE;
   float* s_o = reinterpret_cast<float*>(smem);                  // [MS][ROWS][OPITCH]
-  float* s_m = s_o + MS * ROWS * OPITCH;                         // [W][ROWS], then the block's: [ROWS]
+  float* s_m = reinterpret_cast<float*>(smem + (OBYTES > VBYTES ? OBYTES : VBYTES));   // [W][ROWS], then the block's: [ROWS]
   float* s_l = s_m + (W + 1) * ROWS;                            // [W][ROWS], then the block's: [ROWS]
   const int r0 = rw * WROWS;                                    // my first row inside the block
   if (g4 == 0) {
@@ -418,7 +419,8 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
       s_l[wave * ROWS + r0 + nt * 16 + l16] = lacc[nt][0];
     }
   }
-  __syncthreads();
+  __syncthreads();   // every wave is done with its V tiles too
+  LPP_ATS(2);
   float fscale[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
@@ -706,8 +708,8 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh) {
   const int rows = p.nt * 16;
   const size_t vt = (size_t)p.kw * 2 * 32 * (Dh * 2 + 32);
   const int ms = (size_t)p.kw * rows * (Dh + 4) * 4 <= 96 * 1024 ? p.kw : p.kw / 2;
-  const size_t mg = ((size_t)ms * rows * (Dh + 4) + 2 * (p.kw + 1) * rows) * sizeof(float);
-  p.lds = vt > mg ? vt : mg;
+  const size_t og = (size_t)ms * rows * (Dh + 4) * sizeof(float);
+  p.lds = (vt > og ? vt : og) + (size_t)2 * (p.kw + 1) * rows * sizeof(float);
   return p;
 }
 
