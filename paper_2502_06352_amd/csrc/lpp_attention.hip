@@ -361,7 +361,8 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
     uint64_t vis[NT];
     int gx = c0 + kw;                                 // next general group of this wave
     if (GF >= 1) {
-      constexpr int D = (DH == 64 && NT <= 2) ? 4 : 2;
+      constexpr int D = 2;   // (deeper rings were no faster on long caches and slower on short ones: the
+                             //  eight waves of a block already have sixteen groups in flight)
       Stage<DH> st[D];
       const bool pre = gx < gend;
       if (pre) { visibility(vis, gx); load_any(cst, gx); }
