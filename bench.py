@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 # HBM bytes per launch at config 3 from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (profiles/), scaled
 # by the same counters' reading for a copy of known size; None until measured for a kernel.
-TRAFFIC = {"tree_attention": 29.21e6, "relaxed_verify": 30.20e6}   # config 3; profiles/config3_step_hbm_bytes.txt
+TRAFFIC = {"tree_attention": 29.11e6, "relaxed_verify": 30.20e6}   # config 3; profiles/config3_step_hbm_bytes.txt
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
