@@ -356,8 +356,14 @@ __device__ __forceinline__ void collect_and_walk(MailRound r, int32_t* mail, int
 
 // Sum (max), in wave order, of one float per wave held in LDS; every wave
 // computes the same value the same way.
-template <int NW>
+// WIDE: two broadcast reads and seven additions, a shorter chain than the row shifts (for the
+// build that has eight registers to spare).
+template <int NW, bool WIDE = false>
 __device__ __forceinline__ float combine_sum(const float* s_w, int lane) {
+  if (WIDE && NW == 8) {
+    const float4 a = *reinterpret_cast<const float4*>(s_w), b = *reinterpret_cast<const float4*>(s_w + 4);
+    return ((((((a.x + a.y) + a.z) + a.w) + b.x) + b.y) + b.z) + b.w;
+  }
   float x = lane < NW ? s_w[lane] : 0.f;
   x += dpp_or<0x111, 0xf>(0.f, x);
   x += dpp_or<0x112, 0xf>(0.f, x);
@@ -386,7 +392,9 @@ __device__ __forceinline__ float combine_max(const float* s_w, int lane) {
 // STAG: rows hold their logit loads back by their place in the row table (see the kernel body): a
 // build of its own, because the waits force another order of the first loads.
 template <int NT, int NCH, bool ALIGNED, bool FRONT, bool ALT, bool STAG>
-__global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab tt) {
+// (The plain build is held to 128 registers -- four waves per SIMD, two rows per compute unit: one
+// register more would halve that, which costs far more than a spill.)
+__global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) void verify_rows_kernel(VerifyArgs a, TreeTab tt) {
   constexpr int NW = NT / 64;
   constexpr int NC = NCH * NW;             // cells
   constexpr int CPL = (NC + 63) / 64;      // cells per lane of wave 0 in the final draw
@@ -398,9 +406,9 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
   uint32_t* s_neigh = reinterpret_cast<uint32_t*>(r_lds + ZC + 4);            // [nstage][NT] pairs of 16-bit slots
   float* s_val = reinterpret_cast<float*>(s_neigh + a.nstage * NT);           // ALT: [PASS] gathered values of a pass
   uint32_t* s_incl = reinterpret_cast<uint32_t*>(s_val + PASS);               // ALT: [PASS / 32] membership bits
-  __shared__ float s_max[2][NW];
-  __shared__ float s_sum[2][NW];
-  __shared__ float s_z[2][NW];
+  __shared__ __align__(16) float s_max[2][NW];
+  __shared__ __align__(16) float s_sum[2][NW];
+  __shared__ __align__(16) float s_z[2][NW];
   __shared__ float s_wtot[2][NW];
   __shared__ float s_cell[64 * CPL];
   __shared__ int s_tok[LPP_MAX_ROWS];
@@ -963,12 +971,12 @@ __global__ __launch_bounds__(NT) void verify_rows_kernel(VerifyArgs a, TreeTab t
     if (lane == 0) s_z[ci & 1][w] = z;
     lds_barrier();
     if (ci < 8) LPP_TS(6 + 3 * ci);
-    z = combine_sum<NW>(s_z[ci & 1], lane);
+    z = combine_sum<NW, STAG>(s_z[ci & 1], lane);
     rt_nx = r_lds[t_nx];
     v0_nx = r_lds[pk_nx & 0xFFFFu];
     v1_nx = r_lds[pk_nx >> 16];
     if (z > 0.f) {
-      rs = 1.0f / z;
+      rs = __builtin_amdgcn_rcpf(z);       // (1 ulp: the quotient's own rounding is of that size)
     } else {
       // r' == p: nothing left to resample from, and r stays as it was before this child:
       // put r' back, then undo the move of A's mass
