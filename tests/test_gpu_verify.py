@@ -165,3 +165,18 @@ def test_verify_walk_that_gives_up_is_loud(monkeypatch):
     fresh = lpp.Tree(parent)
     got = run_verify(fresh, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam)
     compare_verify(parent, x, neigh, cfg.V, cfg.vocab_offset, cfg.k, cfg.lam, got)
+
+
+@pytest.mark.parametrize("B,parent", [(120, [-1, 0]), (85, [-1, 0, 0]), (64, [-1, 0, 1, 2])])
+def test_verify_many_items_with_the_whole_grid_resident(B, parent):
+    # Many items of a tiny tree: every item has its own walking block and its own stretch of the
+    # handle's words; B * M stays within one block per compute unit.
+    cfg = CONFIGS[1].scaled(B=B, V=256, ldv=256, k=8)
+    parent = np.array(parent, dtype=np.int32)
+    x = make_verify_inputs(cfg, parent, rho=0.7)
+    neigh = sparse_neighbour_table(make_codebook(cfg), cfg.k, x["tokens"][:, 1:], cfg.V)
+    tree = lpp.Tree(parent)
+    for _ in range(2):
+        got = run_verify(tree, x, neigh, cfg.V, 0, cfg.ldv, cfg.k, cfg.lam)
+        rep = compare_verify(parent, x, neigh, cfg.V, 0, cfg.k, cfg.lam, got)
+    assert rep["walks_compared"] >= B - 2
