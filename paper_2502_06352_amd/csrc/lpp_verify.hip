@@ -20,8 +20,12 @@
 //            reduce its sum
 //   barrier
 // Barriers wait for LDS traffic only, so global stores stay in flight across
-// them.  Rows with the most children are given the lowest block indices.  The
-// last row of a batch item to finish follows the recorded decisions from the root.
+// them; what a child's test leaves behind is written to global memory once, after
+// the row's draw.  Rows with the most children are given the lowest block indices.
+// The walk: the last row of a batch item to finish (a ticket counter) follows the
+// recorded decisions from the root; when the whole grid is resident at once, the
+// block of the first row table entry collects the other rows' results instead
+// (STAG below) and nobody takes a ticket.
 //
 // Variants of the same kernel (template switches, so that the plain build pays for none of them):
 // FRONT  classifier-free guidance and top-k in front of the target softmax (App. B "Models");
@@ -29,6 +33,9 @@
 //        neighbours that would break the bound instead of stopping at the first one (wave 0 walks
 //        the gathered values 64 at a time), and siblings that are distinct draws (a rejected token
 //        leaves p, which is rescaled by 1 / (1 - p(x^))).
+// STAG   the build for a grid that is resident at once (one row per compute unit): rows hold
+//        their logit loads back by chain length, and the walk is done by a wave of the longest
+//        row's block beside that row's draw (collect_and_walk).
 // The additive bound of the earlier LANTERN method is a run-time choice of the cap.
 #include <limits.h>
 #include <math.h>
@@ -775,7 +782,7 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
       const float pt = ALT ? k_pt : exp2_fma(s_dlog[cc], md2) * inv_sd;   // p(x^): the drafter's probability of the token
       const int dec = (s_u[cc] * pt < k_m) ? 1 : 0;                        // u < min(1, mass / p(x^))
       // what the walk needs of this node: a device-scope store, visible to every compute unit
-      // once it has completed (no cache write-back needed before the ticket below)
+      // once it has completed (no cache write-back needed before the ticket, or for the block that walks)
       if (!(STAG && walker))
         __hip_atomic_store(&a.ws_decision[nodebase + c], (P << 1) | dec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
