@@ -69,8 +69,8 @@ int32_t lpp_tree_info(const lpp_tree* tree, int32_t* M, int32_t* depth,
                       int32_t* n_parents, int32_t* max_children);
 
 /* ------------------------------------------------------ neighbour build ---
- * Latent-space neighbourhoods B_k(x) of every code (paper Sec. 2.2: "its k
- * nearest neighbors in latent space"; reused by Sec. 4).
+ * Latent-space neighbourhoods B_k(x) of every code: the k codes closest to x in
+ * the codebook's embedding space (paper Sec. 2.2; reused by Sec. 4).
  *   E      [device] float32 [V, D] row-major codebook; the caller L2-normalises
  *          the rows, so the inner product used here is the cosine similarity.
  *   neigh  [device] int32 [V, k] out; row x = B_k(x), nearest first, x itself in
@@ -88,9 +88,9 @@ int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, int32_t k,
                              int32_t* neigh, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------- tree attention ---
- * One layer of tree-masked decode attention for the flattened tree (paper
- * Sec. 2.1: "flattened and verified ... with an appropriate attention mask";
- * App. A.2: the mask hides every non-ancestor node).  For batch item b, head h,
+ * One layer of tree-masked decode attention: the drafted tree is laid out as one
+ * sequence of rows and checked in a single pass whose mask hides every node that
+ * is not an ancestor (paper Sec. 2.1; App. A.2).  For batch item b, head h,
  * row i:  out[b,h,i,:] = softmax_j(scale * <q[b,h,i], K_j>) V_j  over the keys
  * j in { cached positions [0, seq_len[b]) } U { tree rows t : t == i or t is an
  * ancestor of i }.
@@ -98,7 +98,7 @@ int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, int32_t k,
  *   q, k_tree, v_tree   [device] [B, H, M, Dh] contiguous
  *   k_cache, v_cache    [device] [B, H, S, Dh] contiguous (multi-head: H_kv = H)
  *   seq_len   [device] int32 [B] or NULL (= S for every item); values are clamped to [0, S]
- *   scale     0 selects 1/sqrt(Dh)
+ *   scale     0 selects 1/sqrt(Dh); negative, infinite or NaN is LPP_EINVAL
  *   out       [device] float32 [B, H, M, Dh]
  * Softmax and accumulation are float32; bf16 inputs are multiplied on the matrix
  * cores.  Errors: LPP_EINVAL (null, B/H/S/Dh < 1 -- S = 0 is allowed), LPP_EUNSUPPORTED
@@ -222,7 +222,7 @@ int32_t lpp_relaxed_verify_sampled(const lpp_tree* tree, const float* cond_logit
 /* The same step with every choice in one place: the bound (Sec. 4: LANTERN++'s multiplicative
  * one or the additive one of LANTERN), the front end (App. B "Models"), and the two points the
  * paper leaves open -- how A is picked inside B_k(x^) (Sec. 4 states only the constraint) and
- * how the children of one row were drafted (Sec. 2.1: "samples ... tokens" from p):
+ * how the children of one row were drafted (Sec. 2.1 says only that several are drawn from p):
  *   rule      LPP_RULE_PREFIX   A = the longest nearest-first prefix of B_k(x^) under the bound
  *             LPP_RULE_SKIP     neighbours are visited nearest first; one that would lift the
  *                               sum to the bound or above is passed over and the visit goes on

@@ -502,9 +502,14 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   if (a.nsplit == 1 || !a.counters || !live) return;
 
   // ---- the block of this (head, row range) that finishes last adds the splits up, in split order
-  // The barrier waits until this block's partial has been written (device-scope stores complete
-  // when they are visible to every compute unit); the ticket and the reads below are device-scope
-  // atomics as well, so no cache write-back or invalidate is needed.
+  // Every wave first waits until its own stores of the partial have completed (a device-scope
+  // store is visible to every compute unit once it has completed; the workgroup barrier alone
+  // waits for LDS traffic only), then the barrier gathers the waves, and only then the ticket is
+  // taken.  The ticket and the reads below are device-scope atomics as well, so no cache
+  // write-back or invalidate is needed.
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
+  __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   __syncthreads();
   if (threadIdx.x == 0)
     s_ticket = __hip_atomic_fetch_add(&a.counters[bh * a.msplits + ms], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -755,7 +760,7 @@ int32_t tree_attention_impl(const lpp_tree* tree, int32_t dtype, int32_t out_dty
   if (B < 1 || H < 1 || S < 0 || Dh < 1) return LPP_EINVAL;
   if (Hkv < 1 || Hkv > H || H % Hkv != 0) return LPP_EINVAL;
   if (S > 0 && (!k_cache || !v_cache)) return LPP_EINVAL;
-  if (scale != scale) return LPP_EINVAL;
+  if (!(scale >= 0.f) || scale == INFINITY) return LPP_EINVAL;   // NaN, negative, infinite
   if (Dh != 64 && Dh != 128) return LPP_EUNSUPPORTED;
   if (dtype != LPP_F32 && dtype != LPP_BF16) return LPP_EUNSUPPORTED;
   if (out_dtype != LPP_F32 && out_dtype != LPP_BF16) return LPP_EUNSUPPORTED;

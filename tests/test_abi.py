@@ -109,7 +109,8 @@ def test_attention_and_neighbour_argument_validation(L):
                                     scale, out, ws, wsb, None)
 
     for kw in (dict(tree=None), dict(q=None), dict(kt=None), dict(vt=None), dict(out=None), dict(kc=None),
-               dict(vc=None), dict(B=0), dict(H=0), dict(S=-1), dict(Dh=0), dict(scale=float("nan"))):
+               dict(vc=None), dict(B=0), dict(H=0), dict(S=-1), dict(Dh=0), dict(scale=float("nan")),
+               dict(scale=-1.0), dict(scale=float("inf"))):
         assert attn(**kw) == lpp.LPP_EINVAL, kw
     assert attn(Dh=96) == lpp.LPP_EUNSUPPORTED
     assert attn(dtype=7) == lpp.LPP_EUNSUPPORTED
