@@ -21,6 +21,12 @@ Functions and what pins them (see tests/test_oracle_*.py):
                     enumeration of the output distribution on tiny vocabularies,
                     Monte Carlo, and the bound invariants of Sec. 4.
 
+  float32_error_bound   not part of the method: a first-order bound on what a float32
+                    evaluation loses where Eq. 2's subtraction cancels; the GPU parity
+                    tests add it (capped) to their relative tolerance.  Pinned by a float32
+                    replay of the same rows: never exceeded, and within a stated factor of
+                    the observed error where it matters.
+
   commit_kv         appends the K/V rows of the root and of the accepted path to
                     the cache (App. A.2).  Pinned by the next step's view: plain
                     attention over the committed cache equals the tree-masked
@@ -49,5 +55,6 @@ states holds under the alternatives too, so the choice below is the definition):
 from .knn import build_neighbours, similarity_keys            # noqa: F401
 from .attention import tree_attention, ancestor_mask          # noqa: F401
 from .verify import relaxed_verify, softmax64, inverse_cdf    # noqa: F401
+from .f32_bound import float32_error_bound                    # noqa: F401
 from .commit import commit_kv                                 # noqa: F401
 from .frontend import guided_logits, top_k_filter, sampling_frontend   # noqa: F401

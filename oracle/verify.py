@@ -47,6 +47,27 @@ def _children(parent: np.ndarray) -> List[List[int]]:
     return kids
 
 
+def aggregate_set(r: np.ndarray, nb: np.ndarray, t: int, k: int, cap: float, rule: str):
+    """The set A inside B_k(x^) (Sec. 4) for the current r.  ``nb`` = B_k(x^) nearest first with
+    x^ itself in slot 0.  Returns (|A|, sum_A r, members of A other than x^, the sums that were
+    compared with the cap)."""
+    vals = r[np.asarray(nb[:k], dtype=np.int64)]
+    vals[0] = r[t]                           # x^ itself is always a member
+    if rule == "prefix":
+        C = np.cumsum(vals)                  # nearest-first prefix sums
+        bad = np.flatnonzero(~(C[1:] < cap)) # strict '<' of the bound
+        j = 1 + (int(bad[0]) if bad.size else k - 1)
+        return j, C[j - 1], np.asarray(nb[1:j], dtype=np.int64), C[1:min(j + 1, k)]
+    cum = vals[0]
+    taken, tried = [], []
+    for i in range(1, k):                    # nearest first; a violator is passed over
+        tried.append(cum + vals[i])
+        if cum + vals[i] < cap:
+            cum = cum + vals[i]
+            taken.append(int(nb[i]))
+    return 1 + len(taken), cum, np.asarray(taken, dtype=np.int64), np.asarray(tried)
+
+
 def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits: np.ndarray,
                    vocab_offset: int, V: int, tokens: np.ndarray, neigh: np.ndarray,
                    k: int, lam: float, u_accept: np.ndarray, u_final: np.ndarray,
@@ -58,13 +79,7 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
     q_tok, p_tok, final_tok_all; accept_len [B], path [B,depth] (-1 padded),
     final_token [B].  Diagnostics: bound_margin = min_j |cum_j - lam*r(x^)| /
     (lam*r(x^)) over the prefix sums that were compared (inf if none);
-    final_cdf [B,M,V] (cumulative, unnormalised) if requested;
-    mass_err, q_tok_err, p_tok_err = first-order bounds on the absolute error that an
-    implementation working in float32 can have in mass, q_tok, p_tok: Eq. 2 subtracts p from
-    the adjusted target, and where the two nearly cancel (a sibling that repeats a token
-    whose adjusted target mass is close to p) what is left carries the rounding of both
-    operands, divided by the normaliser.  The bound is carried through the siblings with
-    2^-22 per value (a few float32 roundings) as the unit.
+    final_cdf [B,M,V] (cumulative, unnormalised) if requested.
 
     ``bound``: "multiplicative" (Sec. 4, LANTERN++: sum_A r < lam * r(x^)) or "additive" (the
     earlier LANTERN bound as Sec. 4 prints it: sum_A r < delta, with ``lam`` holding delta).  In
@@ -103,8 +118,6 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
     q_tok = np.zeros((B, M)); p_tok = np.zeros((B, M))
     n_agg = np.zeros((B, M), dtype=np.int32)
     margin = np.full((B, M), np.inf)
-    mass_err = np.zeros((B, M)); q_tok_err = np.zeros((B, M)); p_tok_err = np.zeros((B, M))
-    eps = 2.0 ** -22
     final_all = np.zeros((B, M), dtype=np.int32)
     accept_len = np.zeros(B, dtype=np.int32)
     path = np.full((B, max(max_depth, 1)), -1, dtype=np.int32)
@@ -119,38 +132,14 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
             r = q.copy()
             if kids[P]:
                 p = softmax64(drafter_logits[b, P])[off:off + V]
-                r_err = eps * r                      # bound on the float32 error of each r(x) ...
-                p_err = eps * p                      # ... and p(x)
                 for c in kids[P]:
                     t = int(tokens[b, c])
                     nb = neigh[t]
                     cap = lam * r[t] if bound == "multiplicative" else lam
-                    vals = r[np.asarray(nb[:k], dtype=np.int64)]
-                    vals[0] = r[t]                       # x^ itself is always a member
-                    if rule == "prefix":
-                        C = np.cumsum(vals)                  # nearest-first prefix sums
-                        bad = np.flatnonzero(~(C[1:] < cap)) # strict '<' of the bound
-                        j = 1 + (int(bad[0]) if bad.size else k - 1)
-                        cum = C[j - 1]
-                        members = np.asarray(nb[1:j], dtype=np.int64)
-                        seen = C[1:min(j + 1, k)]            # the sums that were compared
-                    else:
-                        cum = vals[0]
-                        taken, tried = [], []
-                        for i in range(1, k):                # nearest first; a violator is passed over
-                            tried.append(cum + vals[i])
-                            if cum + vals[i] < cap:
-                                cum = cum + vals[i]
-                                taken.append(int(nb[i]))
-                        j = 1 + len(taken)
-                        members = np.asarray(taken, dtype=np.int64)
-                        seen = np.asarray(tried)
+                    j, cum, members, seen = aggregate_set(r, nb, t, k, cap, rule)
                     if cap > 0 and seen.size:
                         margin[b, c] = np.min(np.abs(seen - cap)) / cap
                     mass[b, c] = cum
-                    mass_err[b, c] = r_err[t] + r_err[members].sum()
-                    q_tok_err[b, c] = r_err[t]
-                    p_tok_err[b, c] = p_err[t]
                     n_agg[b, c] = j
                     q_tok[b, c] = r[t]
                     p_tok[b, c] = p[t]
@@ -164,26 +153,12 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
                     res = np.maximum(r2 - p, 0.0)
                     Z = res.sum()
                     if Z > 0:
-                        e2 = r_err.copy()
-                        e2[members] = 0.0
-                        e2[t] = mass_err[b, c]
-                        d_err = e2 + p_err + eps * (r2 + p)          # error of r2 - p before the clamp
-                        live = (res > 0) | (np.abs(r2 - p) <= d_err)  # entries that are, or could be, positive
-                        z_err = d_err[live].sum()
-                        r = res / Z
-                        r_err = np.where(live, d_err, 0.0) / Z + r * (z_err / Z) + eps * r
+                        r = res / Z                      # else r stays (r' == p: c is accepted with probability 1)
                     if siblings == "without_replacement":
                         left = 1.0 - p[t]                # what the other tokens hold of p
-                        left_err = p_err[t] + eps
                         p = p.copy()
                         p[t] = 0.0
-                        if left > 0:
-                            p = p / left
-                            p_err = p_err / left + p * (left_err / left) + eps * p
-                            p_err[t] = 0.0
-                        else:
-                            p = np.zeros_like(p)
-                            p_err = np.zeros_like(p)
+                        p = p / left if left > 0 else np.zeros_like(p)
             final_all[b, P] = inverse_cdf(r, float(u_final[b, P]))
             if keep_final_cdf:
                 final_cdf[b, P] = np.cumsum(r)
@@ -201,7 +176,7 @@ def relaxed_verify(parent: np.ndarray, target_logits: np.ndarray, drafter_logits
     out = {"decision": decision, "ratio": ratio, "mass": mass, "n_agg": n_agg,
            "q_tok": q_tok, "p_tok": p_tok, "final_tok_all": final_all,
            "accept_len": accept_len, "path": path, "final_token": final_token,
-           "bound_margin": margin, "mass_err": mass_err, "q_tok_err": q_tok_err, "p_tok_err": p_tok_err}
+           "bound_margin": margin}
     if keep_final_cdf:
         out["final_cdf"] = final_cdf
     return out

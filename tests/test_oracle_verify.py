@@ -217,22 +217,42 @@ def test_depth2_walk_and_bonus_enumeration():
 
 
 # ------------------------------------------------------------------ Monte Carlo
-def test_monte_carlo_unrelaxed_matches_target():
-    g = np.random.default_rng(2025)
-    V, n_sib, n = 6, 2, 30000
-    q = g.dirichlet(np.ones(V) * 0.7); p = g.dirichlet(np.ones(V) * 0.7)
+def _monte_carlo_chunk(args):
+    """First emitted tokens of n seeded runs of the oracle at a root with two drafted children
+    (a worker of the test below: tokens from p, uniforms, then the oracle's own decisions and walk)."""
+    seed, n, q, p = args
+    g = np.random.default_rng(seed)
+    V = len(q)
     parent = np.array([-1, 0, 0])
-    toks = np.concatenate([np.zeros((n, 1), int), g.choice(V, size=(n, n_sib), p=p)], axis=1).astype(np.int32)
+    toks = np.concatenate([np.zeros((n, 1), int), g.choice(V, size=(n, 2), p=p)], axis=1).astype(np.int32)
     tl = np.broadcast_to(_logits(q), (n, 3, V)); dl = np.broadcast_to(_logits(p), (n, 3, V))
     neigh = np.array([np.roll(np.arange(V), -i) for i in range(V)])
     o = relaxed_verify(parent, tl, dl, 0, V, toks, neigh, 1, 2.0, g.random((n, 3)), g.random((n, 3)))
     first = np.where(o["accept_len"] > 0, toks[np.arange(n), np.maximum(o["path"][:, 0], 0)], o["final_token"])
-    freq = np.bincount(first, minlength=V) / n
+    return np.bincount(first, minlength=V)
+
+
+def test_monte_carlo_unrelaxed_matches_target():
+    # 10^6 seeded runs (eight chunks with seeds of their own, a few worker processes): with A = {x^}
+    # the first emitted token follows the target exactly (App. A.2, Eq. 1-2)
+    from concurrent.futures import ProcessPoolExecutor
+    g = np.random.default_rng(2025)
+    V, n_chunks, per = 6, 8, 125000
+    n = n_chunks * per
+    q = g.dirichlet(np.ones(V) * 0.7); p = g.dirichlet(np.ones(V) * 0.7)
+    jobs = [(2025_000 + i, per, q, p) for i in range(n_chunks)]
+    with ProcessPoolExecutor(max_workers=4) as pool:
+        counts = sum(pool.map(_monte_carlo_chunk, jobs))
+    assert counts.sum() == n >= 10 ** 6
+    freq = counts / n
     assert np.all(np.abs(freq - q) < 4 * np.sqrt(q * (1 - q) / n) + 1e-9)
     chi2 = (n * (freq - q) ** 2 / q).sum()
     assert chi2 < 25.7                                 # chi^2_{5}, p = 1e-4
     # and a deliberately wrong target is rejected by the same statistic
     assert (n * (freq - p) ** 2 / p).sum() > 25.7
+    # ... and so is a target that is off by one percent of its mass (the resolution 10^6 runs buy)
+    q_off = q.copy(); q_off[0] += 0.01 * (1 - q[0]); q_off[1:] *= 0.99
+    assert (n * (freq - q_off) ** 2 / q_off).sum() > 25.7
 
 
 # ------------------------------------------------------- bound invariants (Sec. 4)
