@@ -70,8 +70,10 @@ def test_verify_row_with_more_children_than_a_wave_has_lanes(B):
 
 def test_verify_more_items_than_walk_counters():
     cfg = CONFIGS[1].scaled(V=64, ldv=64, k=4, N=3, branching=(2, 1), B=4100)
-    rep = _verify_case(cfg, rho=0.9)
-    assert rep["walks_compared"] > 4000
+    # (tiny vocabulary, drafter close to the target: siblings often repeat a token, the input on which
+    #  Eq. 2's cancellation shows -- up to 0.2 % of the values may need the float32 allowance here)
+    rep = _verify_case(cfg, rho=0.9, max_slack_used=24)
+    assert rep["walks_compared"] > 4000 and rep["max_slack_rel"] < 5e-3
 
 
 def test_verify_longest_neighbour_lists():
