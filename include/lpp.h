@@ -187,6 +187,25 @@ int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_logits,
                            const float* u_accept, const float* u_final,
                            const lpp_verify_out* out, void* ws, size_t ws_bytes, void* stream);
 
+/* lpp_relaxed_verify for callers that cannot hand over (or allocate) a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid device allocation.  The walk words that
+ * lpp_relaxed_verify keeps in `ws` live in a static device array inside the library instead
+ * (2 * LPP_STATIC_MAX_NODES int32 = 512 KiB, held by every GPU the library runs on until the process
+ * ends).  The call allocates and frees nothing; everything else -- arguments, outputs, kernels,
+ * results bit for bit -- is as for lpp_relaxed_verify.  All calls on one GPU share that array and
+ * it keeps the last call's contents (every word a call reads it has written before): two calls
+ * whose kernels may overlap on one GPU (different streams, different threads) race; order them.
+ * Errors: as lpp_relaxed_verify (no LPP_ENOWORKSPACE), plus LPP_EUNSUPPORTED when
+ * B * M > LPP_STATIC_MAX_NODES or the device index is 64 or more.
+ */
+#define LPP_STATIC_MAX_NODES 65536
+int32_t lpp_relaxed_verify_static(const lpp_tree* tree, const float* target_logits,
+                                  const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                                  int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
+                                  int32_t kstride, int32_t k, float lambda,
+                                  const float* u_accept, const float* u_final,
+                                  const lpp_verify_out* out, void* stream);
+
 /* The same step under the additive bound of the earlier LANTERN method, which the paper's Sec. 4
  * states next to its own:  A = longest nearest-first prefix of B_k(x^) with
  *     sum_{x in A} r(x) < delta        (x^ always in A; r normalised),

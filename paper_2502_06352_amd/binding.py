@@ -63,6 +63,9 @@ def lib() -> C.CDLL:
     L.lpp_relaxed_verify.restype = i32
     L.lpp_relaxed_verify.argtypes = [vp, vp, vp, i64, i32, i32, i32, vp, vp, i32, i32, f32, vp, vp,
                                      C.POINTER(VerifyOut), vp, sz, vp]
+    L.lpp_relaxed_verify_static.restype = i32
+    L.lpp_relaxed_verify_static.argtypes = [vp, vp, vp, i64, i32, i32, i32, vp, vp, i32, i32, f32, vp, vp,
+                                            C.POINTER(VerifyOut), vp]
     L.lpp_relaxed_verify_additive.restype = i32
     L.lpp_relaxed_verify_additive.argtypes = L.lpp_relaxed_verify.argtypes
     L.lpp_relaxed_verify_sampled.restype = i32
@@ -161,6 +164,17 @@ def lpp_relaxed_verify(tree: Tree, target_logits, drafter_logits, ldv: int, voca
            "lpp_relaxed_verify")
 
 
+def lpp_relaxed_verify_static(tree: Tree, target_logits, drafter_logits, ldv: int, vocab_offset: int, V: int,
+                              B: int, tokens, neigh, kstride: int, k: int, lam: float, u_accept, u_final,
+                              out: dict, stream=None) -> None:
+    """As lpp_relaxed_verify, without a workspace: the library's static device array holds the walk words."""
+    vo = VerifyOut(**{n: _ptr(out.get(n)) for n, _ in VerifyOut._fields_})
+    _check(lib().lpp_relaxed_verify_static(tree.handle, _ptr(target_logits), _ptr(drafter_logits), ldv, vocab_offset,
+                                           V, B, _ptr(tokens), _ptr(neigh), kstride, k, lam, _ptr(u_accept),
+                                           _ptr(u_final), C.byref(vo), _stream(stream)),
+           "lpp_relaxed_verify_static")
+
+
 def lpp_relaxed_verify_additive(tree: Tree, target_logits, drafter_logits, ldv: int, vocab_offset: int, V: int,
                                 B: int, tokens, neigh, kstride: int, k: int, delta: float, u_accept, u_final,
                                 out: dict, ws, stream=None) -> None:
@@ -216,3 +230,4 @@ def lpp_relaxed_verify_sampled(tree: Tree, cond_logits, uncond_logits, cfg_scale
                                             C.byref(vo), _ptr(ws),
                                             0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
            "lpp_relaxed_verify_sampled")
+

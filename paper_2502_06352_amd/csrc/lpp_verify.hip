@@ -42,6 +42,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "lpp_internal.h"
 
@@ -1336,6 +1337,52 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
                                       size_t ws_bytes, void* stream) {
   return relaxed_verify_impl(0, 0, 0, false, nullptr, 0.f, 0, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
                              kstride, k, lambda, u_accept, u_final, out, ws, ws_bytes, stream);
+}
+
+// ---- the entry point that allocates nothing.  Its walk words (what lpp_relaxed_verify keeps in
+// the caller's workspace) live in a file-scope device array.  In host code the array's name is
+// only a stand-in for the symbol: the device address is asked for once per device and kept.
+#define LPP_STATIC_SCRATCH_BYTES (2 * (size_t)LPP_STATIC_MAX_NODES * sizeof(int32_t))
+static __device__ __align__(256) unsigned char scratch[LPP_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (each device holds its own copy).
+int32_t static_scratch(void** out) {
+  int dev = -1;
+  LPP_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return LPP_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    LPP_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return LPP_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return LPP_OK;
+}
+}  // namespace
+
+extern "C" int32_t lpp_relaxed_verify_static(const lpp_tree* tree, const float* target_logits,
+                                             const float* drafter_logits, int64_t ldv, int32_t vocab_offset,
+                                             int32_t V, int32_t B, const int32_t* tokens, const int32_t* neigh,
+                                             int32_t kstride, int32_t k, float lambda, const float* u_accept,
+                                             const float* u_final, const lpp_verify_out* out, void* stream) {
+  if (!tree) return LPP_EINVAL;
+  if (B >= 1 && (int64_t)B * tree->M > LPP_STATIC_MAX_NODES) return LPP_EUNSUPPORTED;
+  void* ws = nullptr;
+  if (tree->d_counters) {       // (a host-only handle goes on to argument validation and fails there with LPP_EHIP)
+    const int32_t st = static_scratch(&ws);
+    if (st != LPP_OK) return st;
+  } else {
+    ws = reinterpret_cast<void*>(uintptr_t(256));   // never dereferenced: no device, nothing is launched
+  }
+  return relaxed_verify_impl(0, 0, 0, false, nullptr, 0.f, 0, tree, target_logits, drafter_logits, ldv, vocab_offset, V, B, tokens, neigh,
+                             kstride, k, lambda, u_accept, u_final, out, ws, LPP_STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int32_t lpp_relaxed_verify_additive(const lpp_tree* tree, const float* target_logits,

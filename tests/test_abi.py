@@ -151,6 +151,17 @@ def test_variant_entry_points_validate_like_the_plain_ones(L):
     assert opts_call(VerifyOptions(**good), k=1025) == lpp.LPP_EINVAL            # k > V
     assert opts_call(VerifyOptions(**good), k=4097, V=8192) == lpp.LPP_EUNSUPPORTED   # k > LPP_MAX_K
 
+    def static_call(tree=t, target=FAKE, B=1, k=16, lam=2.0, o=out):
+        return L.lpp_relaxed_verify_static(tree.handle if tree else None, target, FAKE, 1024, 0, 1024, B, FAKE, FAKE,
+                                           16, k, lam, FAKE, FAKE, C.byref(o) if o is not None else None, None)
+
+    for kw in (dict(tree=None), dict(target=None), dict(B=0), dict(k=17), dict(lam=float("nan")), dict(o=None)):
+        assert static_call(**kw) == lpp.LPP_EINVAL, kw
+    assert static_call(B=65536 // 4 + 1) == lpp.LPP_EUNSUPPORTED       # B * M beyond the static array
+    import torch
+    if not torch.cuda.is_available():
+        assert static_call() == lpp.LPP_EHIP
+
     def gqa(H=4, Hkv=2, out_dtype=lpp.LPP_F32, dtype=lpp.LPP_BF16):
         return L.lpp_tree_attention_gqa(t.handle, dtype, out_dtype, FAKE, FAKE, FAKE, FAKE, FAKE, None, 1, H, Hkv,
                                         64, 64, 0.0, FAKE, FAKE, 1 << 26, None)
