@@ -21,9 +21,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
-# HBM bytes per launch at config 3 from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (profiles/), scaled
-# by the same counters' reading for a copy of known size; None until measured for a kernel.
-TRAFFIC = {"tree_attention": 29.11e6, "relaxed_verify": 30.20e6}   # config 3; profiles/config3_step_hbm_bytes.txt
+# HBM bytes per launch (fetched + written) per workload config from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs of this script (summaries under profiles/), scaled by the same counters' reading for a copy
+# of known size; a kernel that is not listed has not been measured (reported as null).
+TRAFFIC = {3: {"tree_attention": 29.11e6, "relaxed_verify": 30.20e6}}
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
@@ -44,6 +45,10 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload config 1..5 (3 = the metric's shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rotate", action="store_true", help="one replica only (cache-resident inputs)")
+    ap.add_argument("--no-cached", action="store_true",
+                    help="leave out the cache-resident pass (so that a kernel trace of this run holds HBM-resident "
+                         "calls only)")
+    ap.add_argument("--no-knn-timing", action="store_true", help="build the neighbour table once, untimed")
     ap.add_argument("--frontend", action="store_true",
                     help="verify through lpp_relaxed_verify_sampled (guidance 3.0 + top-k 2000 fused; reads one more "
                          "target row set); not the headline configuration")
@@ -117,13 +122,13 @@ def main():
     lpp.lpp_build_neighbours(dE, k, neigh, knn_ws)         # warm-up / result used below
     torch.cuda.synchronize()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    knn_reps = 3
+    knn_reps = 0 if args.no_knn_timing else 3
     ev[0].record()
     for _ in range(knn_reps):
         lpp.lpp_build_neighbours(dE, k, neigh, knn_ws)
     ev[1].record()
     torch.cuda.synchronize()
-    knn_ms = ev[0].elapsed_time(ev[1]) / knn_reps
+    knn_ms = ev[0].elapsed_time(ev[1]) / knn_reps if knn_reps else None
     del knn_ws
 
     if args.calibrate_copy:
@@ -242,10 +247,6 @@ def main():
             for i in range(n % R):
                 g_one[i].replay()
 
-        def run_kernel(g, n):          # n launches of one kernel, R per replay
-            for _ in range(n // R):
-                g.replay()
-            return (n // R) * R
     except Exception as e:             # pragma: no cover - depends on the runtime
         launch = "eager (graph capture failed: %s)" % type(e).__name__
         g_attn = g_ver = g_same = None
@@ -254,93 +255,149 @@ def main():
             for i in range(n):
                 step(i)
 
-        def run_kernel(g, n):
-            fn = attention if run_kernel.which == "a" else verify
-            for i in range(n):
-                fn(reps[i % R])
-            return n
-
-    # ---- timed region: W warm-up steps, then exactly K steps between synchronisations
+    # ---- timed region: W warm-up steps, then exactly K steps between synchronisations.  With
+    # graphs, a run of up to 512 steps is ONE graph of exactly that many steps (replicas in rotation),
+    # so that a short run pays one launch, not one per replica round.
+    g_k = None
+    if launch == "hipgraph" and args.steps <= 512:
+        g_k = capture(lambda: [(attention_s(reps[i % R]), verify_s(reps[i % R])) for i in range(args.steps)])
+        g_k.replay()                   # (its first replay uploads the graph: kept out of the timed region)
+        torch.cuda.synchronize()
     run_steps(args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run_steps(args.steps)
+    if g_k is not None:
+        g_k.replay()
+    else:
+        run_steps(args.steps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     steps_per_s = 1e3 / ms_per_step
     mean_accept = float(torch.stack([d["vout"]["accept_len"] for d in reps]).float().mean().item())
 
+    # ---- distributions: HIP events on the launch stream between back-to-back graph replays (R
+    # launches each), at least 200 of them whatever --steps says; per-launch time = replay time / R
+    def replay_samples(g, fallback, n_replays, per):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_replays + 1)]
+        for _ in range(3):
+            g.replay() if g is not None else fallback()
+        evs[0].record()
+        for i in range(n_replays):
+            g.replay() if g is not None else fallback()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        return np.array([evs[i].elapsed_time(evs[i + 1]) / per for i in range(n_replays)])
+
+    def dist(x):
+        return {"mean": float(x.mean()), "median": float(np.median(x)), "p10": float(np.percentile(x, 10)),
+                "p90": float(np.percentile(x, 90)), "samples": int(x.size)}
+
+    n_rep_d = max(200, args.steps // R)
+    step_d = dist(replay_samples(g_all if launch == "hipgraph" else None, lambda: [step(i) for i in range(R)],
+                                 n_rep_d, R))
+
     # ---- the same step when its inputs are still in the 256 MB last-level cache (one replica over and
     # over: what a step sees whose logits and K/V were written just before it); reported beside the
     # HBM-resident figure above, never in place of it
     cached_ms = None
-    if R > 1:
-        n_c = max(200, min(args.steps, 2000)) // R * R
+    if R > 1 and not args.no_cached:
+        cached_ms = float(np.median(replay_samples(g_same, lambda: [step(0) for _ in range(R)], 60, R)))
 
-        def run_same(n):
-            if g_same is not None:
-                for _ in range(n // R):
-                    g_same.replay()
-            else:
-                for _ in range(n):
-                    step(0)
-        run_same(2 * R)
-        torch.cuda.synchronize()
-        tc0 = time.perf_counter()
-        run_same(n_c)
-        torch.cuda.synchronize()
-        cached_ms = (time.perf_counter() - tc0) * 1e3 / n_c
+    # ---- per-kernel device time: back-to-back launches of one kernel over the rotating replicas
+    # (includes the gap between dependent launches)
+    attn_d = dist(replay_samples(g_attn, lambda: [attention(d) for d in reps], n_rep_d, R * L))   # per launch (one layer)
+    ver_d = dist(replay_samples(g_ver, lambda: [verify(d) for d in reps], n_rep_d, R))
+    attn_ms, verify_ms = attn_d["mean"], ver_d["mean"]
 
-    # ---- per-kernel device time: HIP events on the launch stream around back-to-back launches of
-    # one kernel over the rotating replicas (includes the gap between dependent launches)
-    def device_ms(which):
-        run_kernel.which = which
-        g = g_attn if which == "a" else g_ver
-        ev[0].record()
-        n = run_kernel(g, max(args.steps, R))
-        ev[1].record()
-        torch.cuda.synchronize()
-        return ev[0].elapsed_time(ev[1]) / n
+    # ---- streaming-read ceiling of this device: a plain read of 1 GiB (four times the last-level
+    # cache) by the library's probe kernel, best of a few grid sizes
+    stream_gbs = None
+    try:
+        big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        big.zero_()
+        best = 0.0
+        for blocks in (2048, 4096, 8192, 16384):
+            lpp.lpp_probe_stream_read(big, blocks)
+            torch.cuda.synchronize()
+            ev[0].record()
+            for _ in range(5):
+                lpp.lpp_probe_stream_read(big, blocks)
+            ev[1].record()
+            torch.cuda.synchronize()
+            best = max(best, 5 * big.numel() / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9)
+        stream_gbs = best
+        del big
+    except Exception:                  # pragma: no cover
+        stream_gbs = None
 
-    attn_ms = device_ms("a") / L             # per launch (one layer)
-    verify_ms = device_ms("v")
-    kern = {"tree_attention": {"ms": attn_ms, "bytes": attn_bytes, "GBs": attn_bytes / attn_ms / 1e6},
-            "relaxed_verify": {"ms": verify_ms, "bytes": verify_bytes, "GBs": verify_bytes / verify_ms / 1e6}}
-    dom = max(kern, key=lambda n: kern[n]["ms"])
+    kern = {"tree_attention": {"d": attn_d, "bytes": attn_bytes, "GBs": attn_bytes / attn_ms / 1e6},
+            "relaxed_verify": {"d": ver_d, "bytes": verify_bytes, "GBs": verify_bytes / verify_ms / 1e6}}
+    dom = max(kern, key=lambda n: kern[n]["d"]["mean"])
+    traffic = TRAFFIC.get(cfg.idx, {}) if (L == 1 and not gqa_call and not args.frontend
+                                           and args.rule == "prefix" and args.siblings == "iid") else {}
     roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": kern[dom]["GBs"] / HBM_PEAK_GBS, "traffic": TRAFFIC.get(dom) if cfg.idx == 3 else None,
-                "per_call": {n: {"ms": round(v["ms"], 5), "algorithmic_bytes": v["bytes"],
-                                 "GBs": round(v["GBs"], 1), "frac": round(v["GBs"] / HBM_PEAK_GBS, 4)}
+                "frac": kern[dom]["GBs"] / HBM_PEAK_GBS, "traffic": traffic.get(dom),
+                "stream_read_ceiling_GBs": stream_gbs,
+                "frac_of_stream_read_ceiling": kern[dom]["GBs"] / stream_gbs if stream_gbs else None,
+                "per_call": {n: {"ms": round(v["d"]["mean"], 5), "ms_median": round(v["d"]["median"], 5),
+                                 "ms_p10": round(v["d"]["p10"], 5), "ms_p90": round(v["d"]["p90"], 5),
+                                 "algorithmic_bytes": v["bytes"], "traffic": traffic.get(n),
+                                 "GBs": round(v["GBs"], 1), "frac": round(v["GBs"] / HBM_PEAK_GBS, 4),
+                                 "frac_of_stream_read_ceiling": round(v["GBs"] / stream_gbs, 4) if stream_gbs else None}
                              for n, v in kern.items()},
                 "step_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "ms_per_step_events": {k2: round(v2, 5) if isinstance(v2, float) else v2 for k2, v2 in step_d.items()},
                 "cache_resident_ms_per_step": cached_ms}
-    knn_flops = 2.0 * 2.0 * V * V * cfg.D       # the contraction is swept twice
-    knn = {"ms": knn_ms, "mfma_dtype": "f32", "contraction_TFLOPs": knn_flops / (knn_ms * 1e-3) / 1e12,
-           "frac_of_fp32_mfma_peak": knn_flops / (knn_ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS,
-           "note": "one-time per codebook; whole build incl. select, float64 re-rank and sort"}
+    knn = None
+    if knn_ms:
+        knn_flops = 2.0 * V * V * cfg.D             # the method's contraction: every pair of codes once
+        knn = {"ms": knn_ms, "mfma_dtype": "f32", "contraction_TFLOPs": knn_flops / (knn_ms * 1e-3) / 1e12,
+               "frac_of_fp32_mfma_peak": knn_flops / (knn_ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS,
+               "note": "one-time per codebook; whole build (select, float64 re-rank, ordering) against the 2 V^2 D "
+                       "flops of the definition; sweeps beyond the first are not counted as work"}
 
-    # ---- CPU baseline: the float64 numpy oracle, as it stands, on this host
+    # ---- CPU baseline: the float64 numpy oracle, as it stands, on this host: once held to one
+    # thread, once with the host's threading
     cpu = None
     if not args.no_cpu_baseline and L == 1:      # (the oracle's step has one attention layer)
         from oracle import relaxed_verify, tree_attention
         neigh_h = neigh.cpu().numpy()           # input table for the oracle's verify step
         nb = min(B, 1 if cfg.idx >= 5 else B)
-        n_rep, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and n_rep < 500:     # about 10 s of CPU work
-            t0 = time.perf_counter()
-            tree_attention(att["q"][:nb], att["kc"][:nb], att["vc"][:nb], att["kt"][:nb], att["vt"][:nb], parent)
-            relaxed_verify(parent, ver["target_logits"][:nb], ver["drafter_logits"][:nb], cfg.vocab_offset, V,
-                           ver["tokens"][:nb], neigh_h, k, cfg.lam, ver["u_accept"][:nb], ver["u_final"][:nb])
-            t_cpu += time.perf_counter() - t0
-            n_rep += 1
-        cpu = {"value": n_rep * (nb / B) / t_cpu, "unit": "steps/s", "cores": len(os.sched_getaffinity(0)),
+
+        def oracle_steps(budget_s):
+            n_rep, t_cpu = 0, 0.0
+            while t_cpu < budget_s and n_rep < 500:
+                t0 = time.perf_counter()
+                tree_attention(att["q"][:nb], att["kc"][:nb], att["vc"][:nb], att["kt"][:nb], att["vt"][:nb], parent)
+                relaxed_verify(parent, ver["target_logits"][:nb], ver["drafter_logits"][:nb], cfg.vocab_offset, V,
+                               ver["tokens"][:nb], neigh_h, k, cfg.lam, ver["u_accept"][:nb], ver["u_final"][:nb])
+                t_cpu += time.perf_counter() - t0
+                n_rep += 1
+            return n_rep * (nb / B) / t_cpu, n_rep, t_cpu
+
+        threads_all = len(os.sched_getaffinity(0))
+        one = None
+        try:
+            from threadpoolctl import threadpool_info, threadpool_limits
+            pools = [pi.get("num_threads", 1) for pi in threadpool_info()]
+            threads_all = max(pools) if pools else 1
+            with threadpool_limits(limits=1):
+                one = oracle_steps(8.0)
+        except ImportError:            # pragma: no cover
+            pass
+        v_all, n_rep, t_cpu = oracle_steps(10.0)
+        cpu = {"value": v_all, "unit": "steps/s", "cores": threads_all,
                "kind": "oracle", "sample": f"{nb} of {B} batch items of one step, {n_rep} times "
-               f"({t_cpu:.1f} s of CPU work; numpy float64, BLAS threads as configured by the host)"}
+               f"({t_cpu:.1f} s of CPU work; numpy float64, {threads_all} BLAS threads on "
+               f"{len(os.sched_getaffinity(0))} host cores)",
+               "one_thread": None if one is None else {"value": one[0], "unit": "steps/s", "cores": 1,
+                                                       "sample": f"same sample, {one[1]} times ({one[2]:.1f} s)"}}
 
     out = {"metric": "tree_verify_steps_per_sec", "value": steps_per_s, "unit": "steps/s",
            "verified_nodes_per_sec": steps_per_s * B * cfg.N,
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "ms_per_step_median": step_d["median"], "ms_per_step_p10": step_d["p10"], "ms_per_step_p90": step_d["p90"],
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "dtype_note": "verify: f32; attention: %s inputs on MFMA, f32 softmax/accumulate" % cfg.kv_dtype,
            "data": "synthetic",

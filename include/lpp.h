@@ -299,6 +299,16 @@ int32_t lpp_commit_kv(const lpp_tree* tree, int32_t dtype, const void* k_tree, c
                       int32_t B, int32_t H, int32_t S, int32_t Dh, void* k_cache, void* v_cache,
                       int32_t* new_len, void* stream);
 
+/* ----------------------------------------------------------------- probe ---
+ * Measurement aid, not a step of the method: streams `bytes` (rounded down to a multiple of 16)
+ * from src once with `blocks` workgroups of 256 lanes and writes nothing (sink may be NULL; it is
+ * only there so that the reads cannot be optimised away).  Timed by the benchmark as the streaming
+ * read ceiling of the device, next to the published HBM peak.
+ *   src   [device] 16-byte aligned;  sink [device] uint32 or NULL
+ * Errors: LPP_EINVAL (null src, bytes < 16, misaligned, blocks < 1 or > 2^20), LPP_EHIP.
+ */
+int32_t lpp_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, int32_t blocks, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -76,6 +76,8 @@ def lib() -> C.CDLL:
                                           C.POINTER(VerifyOut), vp, sz, vp]
     L.lpp_commit_kv.restype = i32
     L.lpp_commit_kv.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
+    L.lpp_probe_stream_read.restype = i32
+    L.lpp_probe_stream_read.argtypes = [vp, sz, vp, i32, vp]
     _lib = L
     return L
 
@@ -231,3 +233,8 @@ def lpp_relaxed_verify_sampled(tree: Tree, cond_logits, uncond_logits, cfg_scale
                                             0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
            "lpp_relaxed_verify_sampled")
 
+
+def lpp_probe_stream_read(src, blocks: int, sink=None, stream=None) -> None:
+    """Measurement aid: one streaming read of ``src`` (nothing is written)."""
+    _check(lib().lpp_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), blocks,
+                                       _stream(stream)), "lpp_probe_stream_read")

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblpp.so")
-SOURCES = ["lpp_tree.hip", "lpp_verify.hip", "lpp_attention.hip", "lpp_knn.hip", "lpp_commit.hip", "lpp_static.hip"]
+SOURCES = ["lpp_tree.hip", "lpp_verify.hip", "lpp_attention.hip", "lpp_knn.hip", "lpp_commit.hip", "lpp_probe.hip"]
 FLAGS = ["-O3", "-ffp-contract=off", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes", "-Wno-unused-command-line-argument"]
