@@ -727,12 +727,17 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
 
   float p_reg[NCH][4];
   float st = 0.f, sd = 0.f;
+  // STAG: the sums of my chunks of the current r, as the last pass over the row left them: the
+  // draw's cell sums come from these instead of from another read of the row
+  float csum[STAG ? NCH : 1];
+  bool csum_valid = STAG;
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     const float r0 = exp2_fma(tv[j].x, mt2), r1 = exp2_fma(tv[j].y, mt2);
     const float r2 = exp2_fma(tv[j].z, mt2), r3 = exp2_fma(tv[j].w, mt2);
     p_reg[j][0] = exp2_fma(dv[j].x, md2); p_reg[j][1] = exp2_fma(dv[j].y, md2);
     p_reg[j][2] = exp2_fma(dv[j].z, md2); p_reg[j][3] = exp2_fma(dv[j].w, md2);
+    if (STAG) csum[j] = (r0 + r1) + (r2 + r3);
     st += (r0 + r1) + (r2 + r3);
     sd += (p_reg[j][0] + p_reg[j][1]) + (p_reg[j][2] + p_reg[j][3]);
     *reinterpret_cast<float4*>(&r_lds[4 * (tid + NT * j)]) = make_float4(r0, r1, r2, r3);
@@ -968,6 +973,7 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
         res.w = __builtin_amdgcn_fmed3f(rv[j].w * rs - p_reg[j][3], 0.f, 1.f);
       }
       z += (res.x + res.y) + (res.z + res.w);
+      if (STAG) csum[j] = (res.x + res.y) + (res.z + res.w);
       *own = res;
     }
     if (w == (ci >> 6)) {
@@ -985,7 +991,9 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
     v1_nx = r_lds[pk_nx >> 16];
     if (z > 0.f) {
       rs = __builtin_amdgcn_rcpf(z);       // (1 ulp: the quotient's own rounding is of that size)
+      csum_valid = STAG;
     } else {
+      csum_valid = false;                  // (the row is put back below: its sums are read again for the draw)
       // r' == p: nothing left to resample from, and r stays as it was before this child:
       // put r' back, then undo the move of A's mass
 #pragma unroll
@@ -1021,10 +1029,15 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
   {
     // (all reads first, then the NCH reductions side by side: their steps are independent)
     float cs[NCH];
+    if (STAG && csum_valid) {              // uniform
 #pragma unroll
-    for (int j = 0; j < NCH; ++j) {
-      const float4 cv = *reinterpret_cast<const float4*>(&r_lds[4 * (tid + NT * j)]);
-      cs[j] = (cv.x + cv.y) + (cv.z + cv.w);
+      for (int j = 0; j < NCH; ++j) cs[j] = csum[STAG ? j : 0];
+    } else {
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) {
+        const float4 cv = *reinterpret_cast<const float4*>(&r_lds[4 * (tid + NT * j)]);
+        cs[j] = (cv.x + cv.y) + (cv.z + cv.w);
+      }
     }
     wave_inclusive_scan_n<NCH>(cs);
     float mine = 0.f;

@@ -180,3 +180,43 @@ def test_verify_many_items_with_the_whole_grid_resident(B, parent):
         got = run_verify(tree, x, neigh, cfg.V, 0, cfg.ldv, cfg.k, cfg.lam)
         rep = compare_verify(parent, x, neigh, cfg.V, 0, cfg.k, cfg.lam, got)
     assert rep["walks_compared"] >= B - 2
+
+
+@pytest.mark.parametrize("salt", [0, 1, 2, 3])
+@pytest.mark.parametrize("V,k,lam", [(64, 8, 2.0), (48, 48, 6.0), (300, 32, 1.5)])
+def test_verify_resident_grid_siblings_that_repeat_tokens_and_join_later_sets(V, k, lam, salt):
+    # Tiny vocabularies, a drafter close to the target, four siblings under the root and two under each
+    # of them: drafted tokens repeat among siblings, a token that carries an earlier sibling's
+    # mass turns up inside a later sibling's neighbourhood, whole neighbourhoods fit under the bound
+    # (k = V with a wide bound).  B * M = 247 rows: the whole grid is resident at once.
+    cfg = CONFIGS[1].scaled(V=V, ldv=V + 4, vocab_offset=4, k=k, N=12, branching=(4, 2), B=19)
+    parent = static_tree(cfg.branching, cfg.N)
+    x = make_verify_inputs(cfg, parent, rho=0.9, salt=salt)
+    neigh = sparse_neighbour_table(make_codebook(cfg), k, x["tokens"][:, 1:], V)
+    tree = lpp.Tree(parent)
+    got = run_verify(tree, x, neigh, V, cfg.vocab_offset, cfg.ldv, k, lam)
+    rep = compare_verify(parent, x, neigh, V, cfg.vocab_offset, k, lam, got, max_slack_used=12)
+    print(f"V={V} k={k} lam={lam} salt={salt}: {rep}", flush=True)
+    assert rep["nodes"] + rep["skipped_after_tie"] == 19 * 12
+    toks = x["tokens"]
+    kids = [[c for c in range(len(parent)) if parent[c] == P] for P in range(len(parent))]
+    repeats = sum(len(set(toks[b, c])) < len(c) for b in range(19) for c in kids if len(c) > 1)
+    assert repeats > 0 or V > 100, "no sibling repeats a token: the case no longer exercises that path"
+
+
+@pytest.mark.parametrize("k,lam", [(1, 2.0), (8, 0.9), (8, 3.0)])
+def test_verify_identical_drafter_and_target_with_repeated_tokens(k, lam):
+    # p == q on a tiny vocabulary with four siblings: without relaxation (k = 1, or a bound that
+    # admits nobody) every level after a child is empty and r stays as it was, also for a token
+    # that is drafted twice; with relaxation the residual sits on the drafted token alone.
+    V = 32
+    cfg = CONFIGS[1].scaled(V=V, ldv=V, k=k, N=12, branching=(4, 2), B=19)
+    parent = static_tree(cfg.branching, cfg.N)
+    x = make_verify_inputs(cfg, parent, rho=1.0)
+    assert np.array_equal(x["target_logits"], x["drafter_logits"])
+    neigh = sparse_neighbour_table(make_codebook(cfg), k, x["tokens"][:, 1:], V)
+    got = run_verify(lpp.Tree(parent), x, neigh, V, 0, cfg.ldv, k, lam)
+    if k == 1 or lam <= 1:
+        assert np.all(got["decision"][:, 1:] == 1) and np.all(got["ratio"][:, 1:] == 1.0)
+    rep = compare_verify(parent, x, neigh, V, 0, k, lam, got, max_slack_used=12)
+    print(f"k={k} lam={lam}: {rep}", flush=True)
