@@ -25,6 +25,7 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "lpp_internal.h"
@@ -68,6 +69,7 @@ struct AttnArgs {
   float* out;                        // [B,H,M,Dh] float, or bf16 when out_bf16
   float* ws_o;                       // [BH][nsplit][mtiles*16][Dh]   unnormalised partial O
   float* ws_ml;                      // [BH][nsplit][mtiles*16][2]    (reference max in log2 units, sum)
+  uint32_t ws_o_bytes, ws_ml_bytes;  // sizes of the two (each below 2^31 when `counters` is set)
   int32_t* counters;                 // [BH * msplits] zero between calls, or null: separate merge kernel
 #ifdef LPP_ATTN_TIMESTAMPS
   unsigned long long* ts;            // [blocks][16]
@@ -90,6 +92,32 @@ __device__ __forceinline__ void wave_lds_sync() {
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round to nearest even (hardware convert)
   const bf16x2 v = {(__bf16)lo, (__bf16)hi};
   return __builtin_bit_cast(uint32_t, v);
+}
+
+// 16- and 8-byte accesses that are visible device-wide once they have completed (the cache policy
+// of a device-scope atomic, on whole vectors): what the blocks of one head exchange their partial
+// results with inside one launch.  `off` is a byte offset into the buffer behind `rsrc`.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+constexpr int kDeviceScope = 16;     // sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t device_buffer(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ void store_dev(__amdgpu_buffer_rsrc_t r, uint32_t off, float4 v) {
+  const u32x4 x = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+  __builtin_amdgcn_raw_buffer_store_b128(x, r, (int)off, 0, kDeviceScope);
+}
+__device__ __forceinline__ void store_dev(__amdgpu_buffer_rsrc_t r, uint32_t off, float2 v) {
+  const u32x2 x = {__float_as_uint(v.x), __float_as_uint(v.y)};
+  __builtin_amdgcn_raw_buffer_store_b64(x, r, (int)off, 0, kDeviceScope);
+}
+__device__ __forceinline__ float4 load_dev4(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, kDeviceScope);
+  return make_float4(__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w));
+}
+__device__ __forceinline__ float2 load_dev2(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  const u32x2 x = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, kDeviceScope);
+  return make_float2(__uint_as_float(x.x), __uint_as_float(x.y));
 }
 
 // four consecutive output elements starting at element index e of the output tensor
@@ -125,7 +153,8 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   constexpr int WROWS = NT * 16;     // rows of a wave
   constexpr int ROWS = RW * WROWS;   // rows of the block
   constexpr int OPITCH = DH + 4;     // floats per row of the merge buffer
-  constexpr int MS = (KW * NT * 16 * (DH + 4) * 4 <= 96 * 1024) ? KW : KW / 2;   // merge slots
+  // merge slots: one per wave if that fits where the V tiles were (or in 96 KB), else half as many
+  constexpr int MS = (KW * NT * 16 * (DH + 4) * 4 <= (KW * 2 * VTILE > 96 * 1024 ? KW * 2 * VTILE : 96 * 1024)) ? KW : KW / 2;
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_ticket;
 
@@ -465,6 +494,7 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   constexpr int C4 = DH / 4;
   const int rows_pad = a.mtiles * 16;
   const int mb = ms * ROWS;                                     // first row of the block
+  const __amdgpu_buffer_rsrc_t dev_o = device_buffer(a.ws_o, a.ws_o_bytes), dev_ml = device_buffer(a.ws_ml, a.ws_ml_bytes);
   for (int idx = threadIdx.x; idx < ROWS * C4; idx += W * 64) {
     const int r = idx / C4, c4 = idx % C4;
     const int m = mb + r;
@@ -484,14 +514,8 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
       const int64_t prow = ((int64_t)bh * a.nsplit + split) * rows_pad + m;
       float* dst = a.ws_o + prow * DH + c4 * 4;
       if (a.counters) {   // read by another block of this launch: stores that are visible device-wide when they complete
-        __hip_atomic_store(dst + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(dst + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(dst + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(dst + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (c4 == 0) {
-          __hip_atomic_store(&a.ws_ml[prow * 2], bm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_store(&a.ws_ml[prow * 2 + 1], bl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        store_dev(dev_o, (uint32_t)((prow * DH + c4 * 4) * 4), v);
+        if (c4 == 0) store_dev(dev_ml, (uint32_t)(prow * 8), make_float2(bm, bl));
       } else {
         *reinterpret_cast<float4*>(dst) = v;
         if (c4 == 0) { a.ws_ml[prow * 2] = bm; a.ws_ml[prow * 2 + 1] = bl; }
@@ -520,23 +544,32 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
     const int r = idx / C4, c4 = idx % C4;
     const int m = mb + r;
     if (m >= M) continue;
-    float mm = kMasked;
-    for (int sp = 0; sp < a.nsplit; ++sp) {
-      const int64_t prow = ((int64_t)bh * a.nsplit + sp) * rows_pad + m;
-      mm = fmaxf(mm, __hip_atomic_load(&a.ws_ml[prow * 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    }
+    // (four splits at a time: all their loads are in flight together)
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float ll = 0.f;
-    for (int sp = 0; sp < a.nsplit; ++sp) {
-      const int64_t prow = ((int64_t)bh * a.nsplit + sp) * rows_pad + m;
-      const float f = __builtin_amdgcn_exp2f(
-          __hip_atomic_load(&a.ws_ml[prow * 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - mm);
-      ll += f * __hip_atomic_load(&a.ws_ml[prow * 2 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const float* src = a.ws_o + prow * DH + c4 * 4;
-      acc.x += f * __hip_atomic_load(src + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      acc.y += f * __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      acc.z += f * __hip_atomic_load(src + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      acc.w += f * __hip_atomic_load(src + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    float ll = 0.f, mm = kMasked;
+    for (int s0 = 0; s0 < a.nsplit; s0 += 4) {
+      float2 ml[4];
+      float4 o[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int sp = min(s0 + u, a.nsplit - 1);                // (a split past the end: read again, weight 0)
+        const int64_t prow = ((int64_t)bh * a.nsplit + sp) * rows_pad + m;
+        ml[u] = load_dev2(dev_ml, (uint32_t)(prow * 8));
+        o[u] = load_dev4(dev_o, (uint32_t)((prow * DH + c4 * 4) * 4));
+      }
+      float nm = mm;
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (s0 + u < a.nsplit) nm = fmaxf(nm, ml[u].x);
+      const float keep = __builtin_amdgcn_exp2f(mm - nm);       // (the first batch: exp2(-huge) = 0 on zeros)
+      acc.x *= keep; acc.y *= keep; acc.z *= keep; acc.w *= keep; ll *= keep;
+      mm = nm;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float f = s0 + u < a.nsplit ? __builtin_amdgcn_exp2f(ml[u].x - mm) : 0.f;
+        ll += f * ml[u].y;
+        acc.x += f * o[u].x; acc.y += f * o[u].y; acc.z += f * o[u].z; acc.w += f * o[u].w;
+      }
     }
     const float inv = 1.0f / ll;
     store_out4(a.out, a.out_bf16 != 0, ((int64_t)bh * M + m) * DH + c4 * 4,
@@ -697,6 +730,7 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh) {
   // stream the same K/V out of L2.
   if (p.mtiles <= 4 || Dh != 64) {
     p.nt = p.mtiles == 1 ? 1 : 2;
+    if (const char* e = getenv("LPP_ATTN_NT")) { const int v = atoi(e); if (v == 1 || v == 2) p.nt = v; }   // (experiment)
     p.msplits = (p.mtiles + p.nt - 1) / p.nt;
   } else {
     p.msplits = (p.mtiles + 4) / 5;
@@ -713,7 +747,7 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh) {
   p.nsplit = ns;
   const int rows = p.nt * 16;
   const size_t vt = (size_t)p.kw * 2 * 32 * (Dh * 2 + 32);
-  const int ms = (size_t)p.kw * rows * (Dh + 4) * 4 <= 96 * 1024 ? p.kw : p.kw / 2;
+  const int ms = (size_t)p.kw * rows * (Dh + 4) * 4 <= std::max<size_t>(vt, 96 * 1024) ? p.kw : p.kw / 2;
   const size_t og = (size_t)ms * rows * (Dh + 4) * sizeof(float);
   p.lds = (vt > og ? vt : og) + (size_t)2 * (p.kw + 1) * rows * sizeof(float);
   return p;
@@ -803,8 +837,12 @@ int32_t tree_attention_impl(const lpp_tree* tree, int32_t dtype, int32_t out_dty
   a.rc_H = rc((uint32_t)H); a.rc_nsplit = rc((uint32_t)p.nsplit); a.rc_gq = rc((uint32_t)(H / Hkv));
   a.scale_log2 = scale * 1.44269504088896340736f;
   a.out = out;
-  a.counters = (int64_t)B * H * p.msplits <= LPP_COUNTER_SLOTS ? tree->d_counters + LPP_COUNTER_SLOTS : nullptr;
   const size_t rows = (size_t)B * H * p.nsplit * p.mtiles * 16;
+  const size_t o_bytes = rows * Dh * sizeof(float), ml_bytes = rows * 2 * sizeof(float);
+  // the in-kernel merge of key splits addresses the partials with 32-bit offsets
+  a.counters = ((int64_t)B * H * p.msplits <= LPP_COUNTER_SLOTS && o_bytes < (1u << 31)) ? tree->d_counters + LPP_COUNTER_SLOTS : nullptr;
+  a.ws_o_bytes = (uint32_t)std::min<size_t>(o_bytes, 0x7FFFFFFFu);
+  a.ws_ml_bytes = (uint32_t)std::min<size_t>(ml_bytes, 0x7FFFFFFFu);
 #ifdef LPP_ATTN_TIMESTAMPS
   a.ts = reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(ws) + need);
 #endif
