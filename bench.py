@@ -57,8 +57,10 @@ def main():
     ap.add_argument("--siblings", choices=["iid", "distinct"], default="iid",
                     help="sibling scheme (lpp_relaxed_verify_opts when not the default)")
     ap.add_argument("--layers", type=int, default=1,
-                    help="attention launches per step, each on its own K/V cache (a target's layer count); "
-                         "the headline step has one")
+                    help="attention layers per step, each on its own K/V cache (a target's layer count), through "
+                         "lpp_tree_attention_layers; the headline step has one")
+    ap.add_argument("--layer-loop", action="store_true",
+                    help="with --layers: one lpp_tree_attention call per layer instead of lpp_tree_attention_layers")
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="key/value heads shared by groups of query heads (lpp_tree_attention_gqa); 0 = multi-head")
     ap.add_argument("--out-bf16", action="store_true", help="bf16 attention output (lpp_tree_attention_gqa)")
@@ -166,19 +168,28 @@ def main():
         d["layers"] = [{n: (d[n] if l == 0 else d[n].clone()) for n in ("q", "kc", "vc", "kt", "vt")} for l in range(L)]
         d["out_attn"] = torch.empty((B, H, M, Dh), dtype=torch.bfloat16 if args.out_bf16 else torch.float32,
                                     device=dev)
+        # (several layers: one call, every layer with an output of its own)
+        d["layer_table"] = [dict(q=x["q"], k_cache=x["kc"], v_cache=x["vc"], k_tree=x["kt"], v_tree=x["vt"],
+                                 out=d["out_attn"] if l == 0 else torch.empty_like(d["out_attn"]))
+                            for l, x in enumerate(d["layers"])]
         d["vout"] = {"accept_len": torch.empty((B,), dtype=torch.int32, device=dev),
                      "path": torch.empty((B, depth), dtype=torch.int32, device=dev),
                      "final_token": torch.empty((B,), dtype=torch.int32, device=dev),
                      "decision": torch.empty((B, M), dtype=torch.uint8, device=dev),
                      "ratio": torch.empty((B, M), dtype=torch.float32, device=dev)}
         reps.append(d)
-    attn_ws = torch.empty(max(256, lpp.lpp_tree_attention_workspace(tree, B, H, S, Dh)), dtype=torch.uint8, device=dev)
+    attn_ws = torch.empty(max(256, lpp.lpp_tree_attention_layers_workspace(tree, L, B, H, S, Dh)), dtype=torch.uint8,
+                          device=dev)
     ver_ws = torch.empty(lpp.lpp_relaxed_verify_workspace(tree, B, V, k), dtype=torch.uint8, device=dev)
     dtype = lpp.LPP_BF16 if cfg.kv_dtype == "bf16" else lpp.LPP_F32
     stream = torch.cuda.current_stream()
 
     def attention(d, st=None):
         st = stream if st is None else st
+        if L > 1 and not args.layer_loop:
+            lpp.lpp_tree_attention_layers(tree, dtype, lpp.LPP_BF16 if args.out_bf16 else lpp.LPP_F32, d["layer_table"],
+                                          None, B, H, Hkv, S, Dh, 0.0, attn_ws, st)
+            return
         for x in d["layers"]:
             if gqa_call:
                 lpp.lpp_tree_attention_gqa(tree, dtype, lpp.LPP_BF16 if args.out_bf16 else lpp.LPP_F32, x["q"], x["kc"],

@@ -130,6 +130,32 @@ int32_t lpp_tree_attention_gqa(const lpp_tree* tree, int32_t dtype, int32_t out_
                                int32_t B, int32_t H, int32_t Hkv, int32_t S, int32_t Dh, float scale,
                                void* out, void* ws, size_t ws_bytes, void* stream);
 
+/* Several layers of one step in one launch (paper Sec. 2.1; App. A.2: the target checks the
+ * flattened tree in one forward pass, i.e. this attention once per layer; App. B: the targets
+ * have tens of layers).  Every layer has its own tensors, all of the shapes of
+ * lpp_tree_attention_gqa; tree, seq_len, sizes, scale and types are shared.  The layers' blocks
+ * go out together (up to 16 layers per launch, more in consecutive launches on the stream), so that
+ * one layer's start-up and merge overlap the streaming of the others.  The call does not order
+ * the layers against each other: they must be independent (queries computed beforehand).
+ *   layers   [host] L entries of device pointers (read during the call only)
+ * Workspace: lpp_tree_attention_layers_workspace.  Errors: as lpp_tree_attention_gqa, plus
+ * LPP_EINVAL for L < 1 or a null entry.
+ */
+typedef struct lpp_attention_layer {
+  const void* q;          /* [device] [B, H, M, Dh]   */
+  const void* k_cache;    /* [device] [B, Hkv, S, Dh] */
+  const void* v_cache;    /* [device] [B, Hkv, S, Dh] */
+  const void* k_tree;     /* [device] [B, Hkv, M, Dh] */
+  const void* v_tree;     /* [device] [B, Hkv, M, Dh] */
+  void*       out;        /* [device] [B, H, M, Dh], float32 or bf16 (out_dtype) */
+} lpp_attention_layer;
+size_t  lpp_tree_attention_layers_workspace(const lpp_tree* tree, int32_t L, int32_t B, int32_t H,
+                                            int32_t S, int32_t Dh);
+int32_t lpp_tree_attention_layers(const lpp_tree* tree, int32_t dtype, int32_t out_dtype,
+                                  const lpp_attention_layer* layers, int32_t L, const int32_t* seq_len,
+                                  int32_t B, int32_t H, int32_t Hkv, int32_t S, int32_t Dh, float scale,
+                                  void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------- relaxed verify ---
  * Softmax of every row, relaxed acceptance of every drafted node and the walk
  * down the tree (paper Sec. 4; Sec. 2.2; App. A.2 Eq. 1-2).  For row P with

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     LppError, Tree, lib,
     lpp_build_neighbours, lpp_build_neighbours_workspace,
     lpp_tree_attention, lpp_tree_attention_gqa, lpp_tree_attention_workspace,
+    lpp_tree_attention_layers, lpp_tree_attention_layers_workspace,
     lpp_relaxed_verify, lpp_relaxed_verify_workspace, lpp_relaxed_verify_additive, lpp_relaxed_verify_static,
     lpp_commit_kv, lpp_probe_stream_read, lpp_relaxed_verify_sampled, lpp_relaxed_verify_opts,
     LPP_BOUND_MULTIPLICATIVE, LPP_BOUND_ADDITIVE, LPP_RULE_PREFIX, LPP_RULE_SKIP,

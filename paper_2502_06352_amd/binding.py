@@ -58,6 +58,10 @@ def lib() -> C.CDLL:
     L.lpp_tree_attention.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, vp, sz, vp]
     L.lpp_tree_attention_gqa.restype = i32
     L.lpp_tree_attention_gqa.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, sz, vp]
+    L.lpp_tree_attention_layers_workspace.restype = sz
+    L.lpp_tree_attention_layers_workspace.argtypes = [vp, i32, i32, i32, i32, i32]
+    L.lpp_tree_attention_layers.restype = i32
+    L.lpp_tree_attention_layers.argtypes = [vp, i32, i32, vp, i32, vp, i32, i32, i32, i32, i32, f32, vp, sz, vp]
     L.lpp_relaxed_verify_workspace.restype = sz
     L.lpp_relaxed_verify_workspace.argtypes = [vp, i32, i32, i32]
     L.lpp_relaxed_verify.restype = i32
@@ -148,6 +152,24 @@ def lpp_tree_attention_gqa(tree: Tree, dtype: int, out_dtype: int, q, k_cache, v
                                         _ptr(k_tree), _ptr(v_tree), _ptr(seq_len), B, H, Hkv, S, Dh, scale,
                                         _ptr(out), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                                         _stream(stream)), "lpp_tree_attention_gqa")
+
+
+class AttentionLayer(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("q", "k_cache", "v_cache", "k_tree", "v_tree", "out")]
+
+
+def lpp_tree_attention_layers_workspace(tree: Tree, L: int, B: int, H: int, S: int, Dh: int) -> int:
+    return int(lib().lpp_tree_attention_layers_workspace(tree.handle, L, B, H, S, Dh))
+
+
+def lpp_tree_attention_layers(tree: Tree, dtype: int, out_dtype: int, layers, seq_len, B: int, H: int, Hkv: int,
+                              S: int, Dh: int, scale: float, ws, stream=None) -> None:
+    """``layers``: a sequence of dicts with the tensors q, k_cache, v_cache, k_tree, v_tree, out of one layer each."""
+    arr = (AttentionLayer * len(layers))(*[AttentionLayer(**{n: _ptr(y.get(n)) for n, _ in AttentionLayer._fields_})
+                                           for y in layers])
+    _check(lib().lpp_tree_attention_layers(tree.handle, dtype, out_dtype, arr, len(layers), _ptr(seq_len), B, H, Hkv,
+                                           S, Dh, scale, _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                           _stream(stream)), "lpp_tree_attention_layers")
 
 
 def lpp_relaxed_verify_workspace(tree: Tree, B: int, V: int, k: int) -> int:

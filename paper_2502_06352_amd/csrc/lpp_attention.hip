@@ -26,6 +26,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "lpp_internal.h"
@@ -41,23 +42,20 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 constexpr float kMasked = -1.0e30f;  // finite stand-in for -inf
 constexpr float kLazy = 8.0f;        // log2 of the largest probability weight before a rescale
 
-// Build with -DLPP_ATTN_TIMESTAMPS to record per-block phase times (100 MHz counter) behind the
-// workspace the caller passes; off in the product build.
-#ifdef LPP_ATTN_TIMESTAMPS
-#define LPP_ATS(i)                                                                                   \
-  do {                                                                                               \
-    if (threadIdx.x == 0) a.ts[(int64_t)blockIdx.x * 16 + (i)] = __builtin_amdgcn_s_memrealtime();  \
-  } while (0)
-#else
-#define LPP_ATS(i) do { } while (0)
-#endif
+// Several layers of one step go out in one launch: block index / blocks_per_layer picks the layer,
+// whose tensors are looked up in a table inside the kernel arguments (a wave-uniform index).
+constexpr int kLayersPerLaunch = 16;
+struct LayerPtrs {
+  const void* q; const void* kc; const void* vc; const void* kt; const void* vt;
+  void* out;                         // [B,H,M,Dh] float, or bf16 when out_bf16
+};
 
 struct AttnArgs {
-  const uint16_t* q;
-  const uint16_t* kc;
-  const uint16_t* vc;
-  const uint16_t* kt;
-  const uint16_t* vt;
+  LayerPtrs layer[kLayersPerLaunch];
+  int32_t n_layers;
+  uint32_t blocks_per_layer, rc_bpl;  // (a multiple of 8: every layer maps to the XCDs the same way)
+  int64_t layer_rows;                // partial rows per layer in ws_o / ws_ml
+  int32_t layer_counters;            // counters per layer
   const int32_t* seq_len;
   const uint64_t* anc;
   int32_t B, H, S, M, words;
@@ -66,14 +64,10 @@ struct AttnArgs {
   int32_t nsplit, msplits, mtiles;   // mtiles = ceil(M / 16)
   uint32_t rc_perbh, rc_msplits, rc_H, rc_nsplit, rc_gq;   // ceil(2^32 / d): n / d = mulhi(n, rc) while n d < 2^32
   float scale_log2;                  // scale * log2(e)
-  float* out;                        // [B,H,M,Dh] float, or bf16 when out_bf16
   float* ws_o;                       // [BH][nsplit][mtiles*16][Dh]   unnormalised partial O
   float* ws_ml;                      // [BH][nsplit][mtiles*16][2]    (reference max in log2 units, sum)
   uint32_t ws_o_bytes, ws_ml_bytes;  // sizes of the two (each below 2^31 when `counters` is set)
   int32_t* counters;                 // [BH * msplits] zero between calls, or null: separate merge kernel
-#ifdef LPP_ATTN_TIMESTAMPS
-  unsigned long long* ts;            // [blocks][16]
-#endif
 };
 
 // n / d for wave-uniform operands through the host's reciprocal: scalar multiplies, no division
@@ -161,11 +155,13 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l16 = lane & 15, g4 = lane >> 4;
   const int kw = wave % KW, rw = wave / KW;
-  LPP_ATS(0);
 
   // block -> (batch*head, key split, row split); all blocks of one key/value head (every row range
   // and every query head that reads it) share an XCD and follow each other in launch order
-  const uint32_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const uint32_t lyr = div_rc(blockIdx.x, a.blocks_per_layer, a.rc_bpl);
+  const uint32_t bid = blockIdx.x - lyr * a.blocks_per_layer;
+  const LayerPtrs& L = a.layer[lyr];
+  const uint32_t xcd = bid & 7, slot = bid >> 3;
   const uint32_t per_bh = (uint32_t)(a.nsplit * a.msplits);
   const uint32_t hq = div_rc(slot, per_bh, a.rc_perbh), hr = slot - hq * per_bh;
   const uint32_t kvq = div_rc(hq, (uint32_t)a.gq, a.rc_gq), qg = hq - kvq * (uint32_t)a.gq;
@@ -184,10 +180,12 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   const int GC = (seq + 31) >> 5, GT = (M + 31) >> 5, G = GC + GT;
   const int gbeg = (int)div_rc((uint32_t)(split * G), (uint32_t)a.nsplit, a.rc_nsplit);
   const int gend = (int)div_rc((uint32_t)((split + 1) * G), (uint32_t)a.nsplit, a.rc_nsplit);
-  const uint16_t* kc = a.kc + (int64_t)kvbh * S * DH;
-  const uint16_t* vc = a.vc + (int64_t)kvbh * S * DH;
-  const uint16_t* kt = a.kt + (int64_t)kvbh * M * DH;
-  const uint16_t* vt = a.vt + (int64_t)kvbh * M * DH;
+  const uint16_t* kc = reinterpret_cast<const uint16_t*>(L.kc) + (int64_t)kvbh * S * DH;
+  const uint16_t* vc = reinterpret_cast<const uint16_t*>(L.vc) + (int64_t)kvbh * S * DH;
+  const uint16_t* kt = reinterpret_cast<const uint16_t*>(L.kt) + (int64_t)kvbh * M * DH;
+  const uint16_t* vt = reinterpret_cast<const uint16_t*>(L.vt) + (int64_t)kvbh * M * DH;
+  const uint16_t* qh = reinterpret_cast<const uint16_t*>(L.q) + (int64_t)bh * M * DH;
+  float* const out = reinterpret_cast<float*>(L.out);
 
   // Key groups [0, GF) lie wholly inside the cache: no mask, no bounds.  The others (the ragged
   // end of the cache and the tree keys) go through the general path after them.
@@ -235,7 +233,7 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
     const int m = min(m0 + nt * 16 + l16, M - 1);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-      qb[nt][ks] = __builtin_bit_cast(bf16x8, ld16(a.q + (int64_t)bh * M * DH + (uint32_t)(m * DH + ks * 32 + g4 * 8)));
+      qb[nt][ks] = __builtin_bit_cast(bf16x8, ld16(qh + (uint32_t)(m * DH + ks * 32 + g4 * 8)));
   }
 
   f32x4 oacc[DT][NT], lacc[NT];
@@ -400,7 +398,6 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
       // each wait lets the younger loads stay in flight.
       int g = gbeg + kw;
       const int hl = max(h1 - 1, 0);
-      LPP_ATS(7);
 #pragma unroll
       for (int d = 0; d < D; ++d) load_full(st[d], min(g + d * KW, hl));
       if (pre) { compute_group(cst, gx, vis, kAny); gx += KW; }   // while the ring's loads are in flight
@@ -431,10 +428,6 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   // ---- merge the waves of the block (fixed order => run-to-run identical): every wave brings
   // its O to the block's reference maximum and parks it in LDS; the sum over the waves is taken
   // on the way out
-  LPP_ATS(1);
-#ifdef LPP_ATTN_TIMESTAMPS
-  if (lane == 0) a.ts[(int64_t)blockIdx.x * 16 + 8 + wave] = __builtin_amdgcn_s_memrealtime();
-#endif
   // (the maxima and sums have a place of their own behind the V tiles, so a wave can leave them
   // there as soon as it is done; O is parked over the V tiles once every wave is done with them)
   constexpr int OBYTES = MS * ROWS * OPITCH * 4, VBYTES = KW * 2 * VTILE;
@@ -450,7 +443,6 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
     }
   }
   __syncthreads();   // every wave is done with its V tiles too
-  LPP_ATS(2);
   float fscale[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
@@ -488,7 +480,6 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
     }
   }
   __syncthreads();
-  LPP_ATS(3);
 
   // ---- write: final rows if this block saw every key, else an unnormalised partial
   constexpr int C4 = DH / 4;
@@ -509,9 +500,9 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
     if (a.nsplit == 1) {
       const float inv = 1.0f / bl;
       v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
-      store_out4(a.out, a.out_bf16 != 0, ((int64_t)bh * M + m) * DH + c4 * 4, v);
+      store_out4(out, a.out_bf16 != 0, ((int64_t)bh * M + m) * DH + c4 * 4, v);
     } else {
-      const int64_t prow = ((int64_t)bh * a.nsplit + split) * rows_pad + m;
+      const int64_t prow = lyr * a.layer_rows + ((int64_t)bh * a.nsplit + split) * rows_pad + m;
       float* dst = a.ws_o + prow * DH + c4 * 4;
       if (a.counters) {   // read by another block of this launch: stores that are visible device-wide when they complete
         store_dev(dev_o, (uint32_t)((prow * DH + c4 * 4) * 4), v);
@@ -522,7 +513,6 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
       }
     }
   }
-  LPP_ATS(4);
   if (a.nsplit == 1 || !a.counters || !live) return;
 
   // ---- the block of this (head, row range) that finishes last adds the splits up, in split order
@@ -536,9 +526,8 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
   __atomic_signal_fence(__ATOMIC_SEQ_CST);
   __syncthreads();
   if (threadIdx.x == 0)
-    s_ticket = __hip_atomic_fetch_add(&a.counters[bh * a.msplits + ms], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_ticket = __hip_atomic_fetch_add(&a.counters[lyr * a.layer_counters + bh * a.msplits + ms], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
-  LPP_ATS(5);
   if (s_ticket != a.nsplit - 1) return;
   for (int idx = threadIdx.x; idx < ROWS * C4; idx += W * 64) {
     const int r = idx / C4, c4 = idx % C4;
@@ -553,7 +542,7 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int sp = min(s0 + u, a.nsplit - 1);                // (a split past the end: read again, weight 0)
-        const int64_t prow = ((int64_t)bh * a.nsplit + sp) * rows_pad + m;
+        const int64_t prow = lyr * a.layer_rows + ((int64_t)bh * a.nsplit + sp) * rows_pad + m;
         ml[u] = load_dev2(dev_ml, (uint32_t)(prow * 8));
         o[u] = load_dev4(dev_o, (uint32_t)((prow * DH + c4 * 4) * 4));
       }
@@ -572,12 +561,11 @@ __global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a
       }
     }
     const float inv = 1.0f / ll;
-    store_out4(a.out, a.out_bf16 != 0, ((int64_t)bh * M + m) * DH + c4 * 4,
+    store_out4(out, a.out_bf16 != 0, ((int64_t)bh * M + m) * DH + c4 * 4,
                make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv));
   }
-  LPP_ATS(6);
   if (threadIdx.x == 0)   // ready for the next call
-    __hip_atomic_store(&a.counters[bh * a.msplits + ms], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&a.counters[lyr * a.layer_counters + bh * a.msplits + ms], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Finish the softmax across the key splits of one (batch, head): one lane per 4 output floats.
@@ -592,31 +580,31 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnArgs a) {
   const int m = (int)(row % a.M);
   const int64_t bh = row / a.M;
   const int rows_pad = a.mtiles * 16;
+  const int64_t lbase = (int64_t)blockIdx.y * a.layer_rows;      // this layer's partials
   float mm = kMasked;
-  for (int s = 0; s < a.nsplit; ++s) mm = fmaxf(mm, a.ws_ml[((bh * a.nsplit + s) * rows_pad + m) * 2]);
+  for (int s = 0; s < a.nsplit; ++s) mm = fmaxf(mm, a.ws_ml[(lbase + (bh * a.nsplit + s) * rows_pad + m) * 2]);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float ll = 0.f;
   for (int s = 0; s < a.nsplit; ++s) {
-    const int64_t prow = (bh * a.nsplit + s) * rows_pad + m;
+    const int64_t prow = lbase + (bh * a.nsplit + s) * rows_pad + m;
     const float f = __builtin_amdgcn_exp2f(a.ws_ml[prow * 2] - mm);
     ll += f * a.ws_ml[prow * 2 + 1];
     const float4 v = *reinterpret_cast<const float4*>(a.ws_o + prow * DH + c4 * 4);
     acc.x += f * v.x; acc.y += f * v.y; acc.z += f * v.z; acc.w += f * v.w;
   }
   const float inv = 1.0f / ll;
-  store_out4(a.out, a.out_bf16 != 0, row * DH + c4 * 4,
+  store_out4(reinterpret_cast<float*>(a.layer[blockIdx.y].out), a.out_bf16 != 0, row * DH + c4 * 4,
              make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv));
 }
 
 // ---------------------------------------------------------------- fp32 path
 // One block of 4 waves per (tree row, batch*head); lanes split Dh, waves split keys.
 struct AttnArgsF32 {
-  const float* q; const float* kc; const float* vc; const float* kt; const float* vt;
+  LayerPtrs layer[kLayersPerLaunch];     // blockIdx.z picks the layer
   const int32_t* seq_len; const uint64_t* anc;
   int32_t B, H, S, M, words, Dh;
   int32_t gq, out_bf16;     // query heads per key/value head; out holds bf16 instead of float
   float scale;
-  float* out;
 };
 
 // One block per (tree row, batch*head).  Pass 1: one key per thread, score = scale <q, k>, masked
@@ -634,7 +622,13 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
   int seq = S;
   if (a.seq_len) seq = min(max(a.seq_len[b], 0), S);     // (everything below depends on it anyway)
   const int nkeys = seq + M;
-  if (tid < Dh) s_q[tid] = a.q[((int64_t)bh * M + m) * Dh + tid];
+  const LayerPtrs& L = a.layer[blockIdx.z];
+  const float* const lq = reinterpret_cast<const float*>(L.q);
+  const float* const lkc = reinterpret_cast<const float*>(L.kc);
+  const float* const lvc = reinterpret_cast<const float*>(L.vc);
+  const float* const lkt = reinterpret_cast<const float*>(L.kt);
+  const float* const lvt = reinterpret_cast<const float*>(L.vt);
+  if (tid < Dh) s_q[tid] = lq[((int64_t)bh * M + m) * Dh + tid];
   __syncthreads();
 
   float mx = -INFINITY;
@@ -643,7 +637,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
     const int t = j - seq;
     const bool on = j < seq || ((a.anc[(int64_t)m * a.words + (t >> 6)] >> (t & 63)) & 1ull);
     if (on) {
-      const float* kr = j < seq ? a.kc + ((int64_t)kvbh * S + j) * Dh : a.kt + ((int64_t)kvbh * M + t) * Dh;
+      const float* kr = j < seq ? lkc + ((int64_t)kvbh * S + j) * Dh : lkt + ((int64_t)kvbh * M + t) * Dh;
       float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
       for (int c = 0; c < Dh; c += 4) {
         const float4 kv = *reinterpret_cast<const float4*>(kr + c);
@@ -683,7 +677,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
     for (int u = 0; u < 8; ++u) {
       const int j = min(j0 + 4 * u, nkeys - 1);
       pj[u] = j0 + 4 * u < nkeys ? s_p[j] : 0.f;
-      const float* vr = j < seq ? a.vc + ((int64_t)kvbh * S + j) * Dh : a.vt + ((int64_t)kvbh * M + (j - seq)) * Dh;
+      const float* vr = j < seq ? lvc + ((int64_t)kvbh * S + j) * Dh : lvt + ((int64_t)kvbh * M + (j - seq)) * Dh;
       v0[u] = vr[lane];
       v1[u] = hi ? vr[lane + 64] : 0.f;
     }
@@ -701,11 +695,11 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(AttnArgsF32 a) {
     const float o1 = (s_acc[0][lane + 64] + s_acc[1][lane + 64]) + (s_acc[2][lane + 64] + s_acc[3][lane + 64]);
     const int64_t e = ((int64_t)bh * M + m) * Dh;
     if (a.out_bf16) {
-      __bf16* orow = reinterpret_cast<__bf16*>(a.out) + e;
+      __bf16* orow = reinterpret_cast<__bf16*>(L.out) + e;
       if (lane < Dh) orow[lane] = (__bf16)(o0 / l);
       if (lane + 64 < Dh) orow[lane + 64] = (__bf16)(o1 / l);
     } else {
-      float* orow = a.out + e;
+      float* orow = reinterpret_cast<float*>(L.out) + e;
       if (lane < Dh) orow[lane] = o0 / l;
       if (lane + 64 < Dh) orow[lane + 64] = o1 / l;
     }
@@ -721,8 +715,8 @@ struct AttnPlan {
 // its KW waves take the key groups in turn.  The blocks of a head that differ in the row range
 // read the same keys at about the same time and sit on the same XCD, so that the second read is
 // served by its L2.  Key splits (which cost a pass through the workspace) are only added while
-// the grid would leave compute units idle.
-AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh) {
+// the launch (all its layers) would leave compute units idle.
+AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh, int layers) {
   AttnPlan p;
   p.mtiles = (tree->M + 15) / 16;
   // Up to 64 rows: two tiles per wave and one or two blocks per head (enough blocks to fill the
@@ -730,7 +724,6 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh) {
   // stream the same K/V out of L2.
   if (p.mtiles <= 4 || Dh != 64) {
     p.nt = p.mtiles == 1 ? 1 : 2;
-    if (const char* e = getenv("LPP_ATTN_NT")) { const int v = atoi(e); if (v == 1 || v == 2) p.nt = v; }   // (experiment)
     p.msplits = (p.mtiles + p.nt - 1) / p.nt;
   } else {
     p.msplits = (p.mtiles + 4) / 5;
@@ -738,12 +731,11 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh) {
   }
   p.kw = 8;
   const int G = (S + 31) / 32 + (tree->M + 31) / 32;
-  const int blocks_bh = B * H * p.msplits;
-  int ns = 256 / blocks_bh;                       // one block of 8 waves per compute unit
+  const int64_t blocks_bh = (int64_t)B * H * p.msplits * std::max(1, std::min(layers, kLayersPerLaunch));
+  int ns = (int)std::min<int64_t>(tree->n_cu / blocks_bh, 1 << 20);   // one block of 8 waves per compute unit
   const int max_ns = G / (2 * p.kw);              // at least two key groups per wave
   if (ns > max_ns) ns = max_ns;
   if (ns < 1) ns = 1;
-  if (const char* e = getenv("LPP_ATTN_NSPLIT")) { const int v = atoi(e); if (v >= 1 && v <= G) ns = v; }
   p.nsplit = ns;
   const int rows = p.nt * 16;
   const size_t vt = (size_t)p.kw * 2 * 32 * (Dh * 2 + 32);
@@ -753,116 +745,148 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh) {
   return p;
 }
 
+// Raises the dynamic LDS limit of a kernel when a launch needs more than it was raised to so far.
+int32_t ensure_lds(const void* kern, std::atomic<size_t>& raised, size_t lds) {
+  if (lds > raised.load(std::memory_order_relaxed)) {
+    LPP_HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    raised.store(lds, std::memory_order_relaxed);
+  }
+  return LPP_OK;
+}
+
 template <int DH, int NT, int RW, int KW>
 int32_t launch_bf16(const AttnArgs& a, const AttnPlan& p, hipStream_t s) {
-  static size_t attr_lds = 48 * 1024;   // largest dynamic LDS size this instantiation was enabled for
+  static std::atomic<size_t> raised{48 * 1024};
   auto kern = tree_attn_bf16_kernel<DH, NT, RW, KW>;
-  if (p.lds > attr_lds) {
-    LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds));
-    attr_lds = p.lds;
-  }
-  const int BH = a.B * a.H, KVBH = a.B * a.Hkv;
-  const unsigned blocks = 8u * ((KVBH + 7) / 8) * a.gq * p.nsplit * p.msplits;
-  hipLaunchKernelGGL(kern, dim3(blocks), dim3(RW * KW * 64), p.lds, s, a);
+  const int32_t st = ensure_lds(reinterpret_cast<const void*>(kern), raised, p.lds);
+  if (st != LPP_OK) return st;
+  hipLaunchKernelGGL(kern, dim3(a.blocks_per_layer * (unsigned)a.n_layers), dim3(RW * KW * 64), p.lds, s, a);
   LPP_HIP_TRY(hipGetLastError());
   if (p.nsplit > 1 && !a.counters) {
-    const int64_t total = (int64_t)BH * a.M * (DH / 4);
-    hipLaunchKernelGGL(tree_attn_merge_kernel<DH>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);
+    const int64_t total = (int64_t)a.B * a.H * a.M * (DH / 4);
+    hipLaunchKernelGGL(tree_attn_merge_kernel<DH>, dim3((unsigned)((total + 255) / 256), (unsigned)a.n_layers), dim3(256),
+                       0, s, a);
     LPP_HIP_TRY(hipGetLastError());
   }
   return LPP_OK;
+}
+
+size_t layer_workspace(const AttnPlan& p, int B, int H, int Dh, size_t* o_bytes) {
+  const size_t rows = (size_t)B * H * p.nsplit * p.mtiles * 16;
+  if (o_bytes) *o_bytes = lpp_align_up(rows * Dh * sizeof(float), 256);
+  return lpp_align_up(rows * Dh * sizeof(float), 256) + lpp_align_up(rows * 2 * sizeof(float), 256);
 }
 
 }  // namespace
 
 extern "C" size_t lpp_tree_attention_workspace(const lpp_tree* tree, int32_t B, int32_t H, int32_t S,
                                                int32_t Dh) {
-  if (!tree || B < 1 || H < 1 || S < 0 || (Dh != 64 && Dh != 128)) return 0;
-  const AttnPlan p = plan_attention(tree, B, H, S, Dh);
-  const size_t rows = (size_t)B * H * p.nsplit * p.mtiles * 16;
-  return lpp_align_up(rows * Dh * sizeof(float), 256) + lpp_align_up(rows * 2 * sizeof(float), 256);
+  return lpp_tree_attention_layers_workspace(tree, 1, B, H, S, Dh);
+}
+
+extern "C" size_t lpp_tree_attention_layers_workspace(const lpp_tree* tree, int32_t L, int32_t B, int32_t H,
+                                                      int32_t S, int32_t Dh) {
+  if (!tree || L < 1 || B < 1 || H < 1 || S < 0 || (Dh != 64 && Dh != 128)) return 0;
+  const AttnPlan p = plan_attention(tree, B, H, S, Dh, L);
+  return (size_t)std::min(L, kLayersPerLaunch) * layer_workspace(p, B, H, Dh, nullptr);
 }
 
 namespace {
-int32_t tree_attention_impl(const lpp_tree* tree, int32_t dtype, int32_t out_dtype, const void* q,
-                            const void* k_cache, const void* v_cache, const void* k_tree, const void* v_tree,
-                            const int32_t* seq_len, int32_t B, int32_t H, int32_t Hkv, int32_t S, int32_t Dh,
-                            float scale, void* out_any, void* ws, size_t ws_bytes, void* stream) {
-  float* out = reinterpret_cast<float*>(out_any);
-  if (!tree || !q || !k_tree || !v_tree || !out) return LPP_EINVAL;
+int32_t tree_attention_impl(const lpp_tree* tree, int32_t dtype, int32_t out_dtype, const lpp_attention_layer* layers,
+                            int32_t L, const int32_t* seq_len, int32_t B, int32_t H, int32_t Hkv, int32_t S,
+                            int32_t Dh, float scale, void* ws, size_t ws_bytes, void* stream) {
+  if (!tree || !layers || L < 1) return LPP_EINVAL;
   if (B < 1 || H < 1 || S < 0 || Dh < 1) return LPP_EINVAL;
   if (Hkv < 1 || Hkv > H || H % Hkv != 0) return LPP_EINVAL;
-  if (S > 0 && (!k_cache || !v_cache)) return LPP_EINVAL;
+  for (int32_t l = 0; l < L; ++l) {
+    const lpp_attention_layer& y = layers[l];
+    if (!y.q || !y.k_tree || !y.v_tree || !y.out) return LPP_EINVAL;
+    if (S > 0 && (!y.k_cache || !y.v_cache)) return LPP_EINVAL;
+  }
   if (!(scale >= 0.f) || scale == INFINITY) return LPP_EINVAL;   // NaN, negative, infinite
   if (Dh != 64 && Dh != 128) return LPP_EUNSUPPORTED;
   if (dtype != LPP_F32 && dtype != LPP_BF16) return LPP_EUNSUPPORTED;
   if (out_dtype != LPP_F32 && out_dtype != LPP_BF16) return LPP_EUNSUPPORTED;
   if ((int64_t)B * H > (1 << 24) || (int64_t)B * H * H >= (1ll << 32)) return LPP_EUNSUPPORTED;
   if ((int64_t)S * Dh >= (1ll << 31) || (int64_t)tree->M * Dh >= (1ll << 31)) return LPP_EUNSUPPORTED;   // 32-bit offsets inside one head
-  const size_t need = lpp_tree_attention_workspace(tree, B, H, S, Dh);
+  const size_t need = lpp_tree_attention_layers_workspace(tree, L, B, H, S, Dh);
   if (!ws || ws_bytes < need) return LPP_ENOWORKSPACE;
   if (!tree->d_anc) return LPP_EHIP;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   if (scale == 0.f) scale = 1.0f / sqrtf((float)Dh);
 
-  if (dtype == LPP_F32) {
-    AttnArgsF32 a;
-    a.q = (const float*)q; a.kc = (const float*)k_cache; a.vc = (const float*)v_cache;
-    a.kt = (const float*)k_tree; a.vt = (const float*)v_tree; a.seq_len = seq_len; a.anc = tree->d_anc;
-    a.B = B; a.H = H; a.S = S; a.M = tree->M; a.words = tree->words; a.Dh = Dh; a.scale = scale; a.out = out;
-    a.gq = H / Hkv; a.out_bf16 = out_dtype == LPP_BF16;
-    static size_t attr_lds = 48 * 1024;
-    const size_t lds = (size_t)(S + tree->M) * sizeof(float);
-    if (lds > 144 * 1024) return LPP_EUNSUPPORTED;     // the scores of one row are kept in LDS
-    if (lds > attr_lds) {
-      LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(tree_attn_f32_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-      attr_lds = lds;
+  const AttnPlan p = plan_attention(tree, B, H, S, Dh, L);
+  // up to kLayersPerLaunch layers per launch; the launches of one call follow each other on the
+  // stream and share the workspace
+  for (int32_t l0 = 0; l0 < L; l0 += kLayersPerLaunch) {
+    const int32_t nl = std::min(L - l0, kLayersPerLaunch);
+    if (dtype == LPP_F32) {
+      AttnArgsF32 a;
+      for (int32_t l = 0; l < kLayersPerLaunch; ++l) {
+        const lpp_attention_layer& y = layers[l0 + std::min(l, nl - 1)];
+        a.layer[l] = LayerPtrs{y.q, y.k_cache, y.v_cache, y.k_tree, y.v_tree, y.out};
+      }
+      a.seq_len = seq_len; a.anc = tree->d_anc;
+      a.B = B; a.H = H; a.S = S; a.M = tree->M; a.words = tree->words; a.Dh = Dh; a.scale = scale;
+      a.gq = H / Hkv; a.out_bf16 = out_dtype == LPP_BF16;
+      static std::atomic<size_t> raised{48 * 1024};
+      const size_t lds = (size_t)(S + tree->M) * sizeof(float);
+      if (lds > 144 * 1024) return LPP_EUNSUPPORTED;     // the scores of one row are kept in LDS
+      const int32_t st = ensure_lds(reinterpret_cast<const void*>(tree_attn_f32_kernel), raised, lds);
+      if (st != LPP_OK) return st;
+      hipLaunchKernelGGL(tree_attn_f32_kernel, dim3((unsigned)tree->M, (unsigned)(B * H), (unsigned)nl), dim3(256), lds,
+                         s, a);
+      LPP_HIP_TRY(hipGetLastError());
+      continue;
     }
-    hipLaunchKernelGGL(tree_attn_f32_kernel, dim3((unsigned)tree->M, (unsigned)(B * H)), dim3(256), lds, s, a);
-    LPP_HIP_TRY(hipGetLastError());
-    return LPP_OK;
-  }
 
-  const AttnPlan p = plan_attention(tree, B, H, S, Dh);
-  AttnArgs a;
-  a.q = (const uint16_t*)q; a.kc = (const uint16_t*)k_cache; a.vc = (const uint16_t*)v_cache;
-  a.kt = (const uint16_t*)k_tree; a.vt = (const uint16_t*)v_tree; a.seq_len = seq_len; a.anc = tree->d_anc;
-  a.B = B; a.H = H; a.S = S; a.M = tree->M; a.words = tree->words;
-  a.Hkv = Hkv; a.gq = H / Hkv; a.out_bf16 = out_dtype == LPP_BF16;
-  a.nsplit = p.nsplit; a.msplits = p.msplits; a.mtiles = p.mtiles;
-  auto rc = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((0x100000000ull + d - 1) / d); };
-  a.rc_perbh = rc((uint32_t)(p.nsplit * p.msplits)); a.rc_msplits = rc((uint32_t)p.msplits);
-  a.rc_H = rc((uint32_t)H); a.rc_nsplit = rc((uint32_t)p.nsplit); a.rc_gq = rc((uint32_t)(H / Hkv));
-  a.scale_log2 = scale * 1.44269504088896340736f;
-  a.out = out;
-  const size_t rows = (size_t)B * H * p.nsplit * p.mtiles * 16;
-  const size_t o_bytes = rows * Dh * sizeof(float), ml_bytes = rows * 2 * sizeof(float);
-  // the in-kernel merge of key splits addresses the partials with 32-bit offsets
-  a.counters = ((int64_t)B * H * p.msplits <= LPP_COUNTER_SLOTS && o_bytes < (1u << 31)) ? tree->d_counters + LPP_COUNTER_SLOTS : nullptr;
-  a.ws_o_bytes = (uint32_t)std::min<size_t>(o_bytes, 0x7FFFFFFFu);
-  a.ws_ml_bytes = (uint32_t)std::min<size_t>(ml_bytes, 0x7FFFFFFFu);
-#ifdef LPP_ATTN_TIMESTAMPS
-  a.ts = reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(ws) + need);
-#endif
-  a.ws_o = reinterpret_cast<float*>(ws);
-  a.ws_ml = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(ws) + lpp_align_up(rows * Dh * sizeof(float), 256));
+    AttnArgs a;
+    for (int32_t l = 0; l < kLayersPerLaunch; ++l) {
+      const lpp_attention_layer& y = layers[l0 + std::min(l, nl - 1)];
+      a.layer[l] = LayerPtrs{y.q, y.k_cache, y.v_cache, y.k_tree, y.v_tree, y.out};
+    }
+    a.n_layers = nl;
+    a.seq_len = seq_len; a.anc = tree->d_anc;
+    a.B = B; a.H = H; a.S = S; a.M = tree->M; a.words = tree->words;
+    a.Hkv = Hkv; a.gq = H / Hkv; a.out_bf16 = out_dtype == LPP_BF16;
+    a.nsplit = p.nsplit; a.msplits = p.msplits; a.mtiles = p.mtiles;
+    auto rc = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((0x100000000ull + d - 1) / d); };
+    a.rc_perbh = rc((uint32_t)(p.nsplit * p.msplits)); a.rc_msplits = rc((uint32_t)p.msplits);
+    a.rc_H = rc((uint32_t)H); a.rc_nsplit = rc((uint32_t)p.nsplit); a.rc_gq = rc((uint32_t)(H / Hkv));
+    a.scale_log2 = scale * 1.44269504088896340736f;
+    const int64_t KVBH = (int64_t)B * Hkv;
+    const int64_t bpl = 8 * ((KVBH + 7) / 8) * (H / Hkv) * p.nsplit * p.msplits;
+    if (bpl * nl >= (1ll << 31)) return LPP_EUNSUPPORTED;
+    a.blocks_per_layer = (uint32_t)bpl; a.rc_bpl = rc((uint32_t)bpl);
+    size_t o_layer = 0;
+    const size_t ws_layer = layer_workspace(p, B, H, Dh, &o_layer);
+    (void)ws_layer;
+    a.layer_rows = (int64_t)B * H * p.nsplit * p.mtiles * 16;
+    a.layer_counters = B * H * p.msplits;
+    const size_t o_bytes = (size_t)nl * a.layer_rows * Dh * sizeof(float), ml_bytes = (size_t)nl * a.layer_rows * 2 * sizeof(float);
+    // the in-kernel merge of key splits addresses the partials with 32-bit offsets and needs a
+    // counter per (layer, head, row range)
+    a.counters = ((int64_t)nl * a.layer_counters <= LPP_COUNTER_SLOTS && o_bytes < (1u << 31))
+                     ? tree->d_counters + LPP_COUNTER_SLOTS : nullptr;
+    a.ws_o_bytes = (uint32_t)std::min<size_t>(o_bytes, 0x7FFFFFFFu);
+    a.ws_ml_bytes = (uint32_t)std::min<size_t>(ml_bytes, 0x7FFFFFFFu);
+    a.ws_o = reinterpret_cast<float*>(ws);
+    a.ws_ml = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(ws) + (size_t)std::min(L, kLayersPerLaunch) * o_layer);
 
-#define LPP_ATTN(DHV)                                                        \
-  do {                                                                       \
-    if (p.nt == 1) return launch_bf16<DHV, 1, 1, 8>(a, p, s);                \
-    if (p.nt == 2) return launch_bf16<DHV, 2, 1, 8>(a, p, s);                \
-  } while (0)
-  if (Dh == 64) {
-    LPP_ATTN(64);
-    if (p.nt == 3) return launch_bf16<64, 3, 1, 8>(a, p, s);
-    if (p.nt == 4) return launch_bf16<64, 4, 1, 8>(a, p, s);
-    return launch_bf16<64, 5, 1, 8>(a, p, s);
+    int32_t st = LPP_EUNSUPPORTED;
+    if (Dh == 64) {
+      if (p.nt == 1) st = launch_bf16<64, 1, 1, 8>(a, p, s);
+      else if (p.nt == 2) st = launch_bf16<64, 2, 1, 8>(a, p, s);
+      else if (p.nt == 3) st = launch_bf16<64, 3, 1, 8>(a, p, s);
+      else if (p.nt == 4) st = launch_bf16<64, 4, 1, 8>(a, p, s);
+      else st = launch_bf16<64, 5, 1, 8>(a, p, s);
+    } else {
+      if (p.nt == 1) st = launch_bf16<128, 1, 1, 8>(a, p, s);
+      else if (p.nt == 2) st = launch_bf16<128, 2, 1, 8>(a, p, s);
+    }
+    if (st != LPP_OK) return st;
   }
-  LPP_ATTN(128);
-  return LPP_EUNSUPPORTED;
-#undef LPP_ATTN
+  return LPP_OK;
 }
 }  // namespace
 
@@ -870,8 +894,8 @@ extern "C" int32_t lpp_tree_attention(const lpp_tree* tree, int32_t dtype, const
                                       const void* v_cache, const void* k_tree, const void* v_tree,
                                       const int32_t* seq_len, int32_t B, int32_t H, int32_t S, int32_t Dh,
                                       float scale, float* out, void* ws, size_t ws_bytes, void* stream) {
-  return tree_attention_impl(tree, dtype, LPP_F32, q, k_cache, v_cache, k_tree, v_tree, seq_len, B, H, H, S, Dh,
-                             scale, out, ws, ws_bytes, stream);
+  const lpp_attention_layer y = {q, k_cache, v_cache, k_tree, v_tree, out};
+  return tree_attention_impl(tree, dtype, LPP_F32, &y, 1, seq_len, B, H, H, S, Dh, scale, ws, ws_bytes, stream);
 }
 
 extern "C" int32_t lpp_tree_attention_gqa(const lpp_tree* tree, int32_t dtype, int32_t out_dtype, const void* q,
@@ -879,6 +903,13 @@ extern "C" int32_t lpp_tree_attention_gqa(const lpp_tree* tree, int32_t dtype, i
                                           const void* v_tree, const int32_t* seq_len, int32_t B, int32_t H,
                                           int32_t Hkv, int32_t S, int32_t Dh, float scale, void* out, void* ws,
                                           size_t ws_bytes, void* stream) {
-  return tree_attention_impl(tree, dtype, out_dtype, q, k_cache, v_cache, k_tree, v_tree, seq_len, B, H, Hkv, S,
-                             Dh, scale, out, ws, ws_bytes, stream);
+  const lpp_attention_layer y = {q, k_cache, v_cache, k_tree, v_tree, out};
+  return tree_attention_impl(tree, dtype, out_dtype, &y, 1, seq_len, B, H, Hkv, S, Dh, scale, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t lpp_tree_attention_layers(const lpp_tree* tree, int32_t dtype, int32_t out_dtype,
+                                             const lpp_attention_layer* layers, int32_t L, const int32_t* seq_len,
+                                             int32_t B, int32_t H, int32_t Hkv, int32_t S, int32_t Dh, float scale,
+                                             void* ws, size_t ws_bytes, void* stream) {
+  return tree_attention_impl(tree, dtype, out_dtype, layers, L, seq_len, B, H, Hkv, S, Dh, scale, ws, ws_bytes, stream);
 }

@@ -21,6 +21,7 @@ struct lpp_tree {
   std::vector<uint64_t> anc; // [M * words]
   // device copies (null for a host-only handle)
   int device = -1;
+  int32_t n_cu = 256;        // compute units of that device (launch heuristics)
   int32_t* d_child_ptr = nullptr;  // [M + 1]
   int32_t* d_child_idx = nullptr;  // [max(N, 1)]
   uint64_t* d_anc = nullptr;       // [M * words]

@@ -74,6 +74,11 @@ extern "C" int32_t lpp_tree_create(const int32_t* parent_host, int32_t M, lpp_tr
     return (int32_t)LPP_EHIP;
   };
   if (hipGetDevice(&t->device) != hipSuccess) return fail();
+  {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, t->device) != hipSuccess) return fail();
+    if (v > 0) t->n_cu = v;
+  }
   size_t b_ptr = sizeof(int32_t) * (M + 1), b_idx = sizeof(int32_t) * t->child_idx.size(),
          b_anc = sizeof(uint64_t) * t->anc.size();
   if (hipMalloc((void**)&t->d_child_ptr, b_ptr) != hipSuccess) return fail();
