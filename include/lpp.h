@@ -68,6 +68,24 @@ int32_t lpp_tree_destroy(lpp_tree* tree);
 int32_t lpp_tree_info(const lpp_tree* tree, int32_t* M, int32_t* depth,
                       int32_t* n_parents, int32_t* max_children);
 
+/* The walk of lpp_relaxed_verify when all B * M row blocks of a launch fit the device at once (one
+ * per compute unit) is done by one of the item's row blocks, which waits, with a bound, for the other
+ * rows' results (see lpp_relaxed_verify).  That presumes the launch's blocks are all resident
+ * together: the stream's kernel has the device to itself (no compute-unit mask, no long kernel of
+ * another stream or process in the way).  If the wait ever runs out, the item's accept_len, path and
+ * final_token are -1 for that call and for every later call on the handle, until it is reset:
+ *   lpp_tree_walk_status   [host] gave_up = 1 if that has happened.  Copies one word back from the
+ *                          device: it waits for the device (not for use inside a capture).
+ *   lpp_tree_walk_reset    enqueues on `stream` the kernel that clears that state; the handle is good
+ *                          again for calls ordered after it.
+ *   lpp_tree_set_walk_patience   rounds (about 0.5 us each) the walking block waits: default and maximum
+ *                          2^19; -1 makes the walk give up at once (for tests of the caller's handling).
+ * Errors: LPP_EINVAL (null, rounds < -1), LPP_EHIP (host-only handle, copy or launch failed).
+ */
+int32_t lpp_tree_walk_status(const lpp_tree* tree, int32_t* gave_up);
+int32_t lpp_tree_walk_reset(lpp_tree* tree, void* stream);
+int32_t lpp_tree_set_walk_patience(lpp_tree* tree, int32_t rounds);
+
 /* ------------------------------------------------------ neighbour build ---
  * Latent-space neighbourhoods B_k(x) of every code: the k codes closest to x in
  * the codebook's embedding space (paper Sec. 2.2; reused by Sec. 4).
@@ -189,8 +207,7 @@ int32_t lpp_tree_attention_layers(const lpp_tree* tree, int32_t dtype, int32_t o
  * its row blocks, which waits for the others' results; that wait is bounded, and nobody waits
  * for that block.  Should it ever run out (it cannot unless the other blocks of the launch do
  * not run), accept_len[b], path[b, :] and final_token[b] are set to -1, and so are those of
- * every later call with this handle: make a new one.  LPP_VERIFY_SPIN_LIMIT=-1 in the
- * environment forces that outcome (for tests of the caller's handling).
+ * every later call with this handle until lpp_tree_walk_reset; lpp_tree_walk_status tells.
  */
 typedef struct lpp_verify_out {
   int32_t* accept_len;     /* [device] [B]        number of accepted drafted nodes            */

@@ -48,6 +48,9 @@ def lib() -> C.CDLL:
     L.lpp_tree_create.restype = i32; L.lpp_tree_create.argtypes = [vp, i32, C.POINTER(vp)]
     L.lpp_tree_destroy.restype = i32; L.lpp_tree_destroy.argtypes = [vp]
     L.lpp_tree_info.restype = i32; L.lpp_tree_info.argtypes = [vp] + [C.POINTER(i32)] * 4
+    L.lpp_tree_walk_status.restype = i32; L.lpp_tree_walk_status.argtypes = [vp, C.POINTER(i32)]
+    L.lpp_tree_walk_reset.restype = i32; L.lpp_tree_walk_reset.argtypes = [vp, vp]
+    L.lpp_tree_set_walk_patience.restype = i32; L.lpp_tree_set_walk_patience.argtypes = [vp, i32]
     L.lpp_build_neighbours_workspace.restype = sz
     L.lpp_build_neighbours_workspace.argtypes = [i32, i32, i32]
     L.lpp_build_neighbours.restype = i32
@@ -114,6 +117,17 @@ class Tree:
         v = [C.c_int32() for _ in range(4)]
         _check(lib().lpp_tree_info(self.handle, *[C.byref(x) for x in v]), "lpp_tree_info")
         self.M, self.depth, self.n_parents, self.max_children = [x.value for x in v]
+
+    def walk_gave_up(self) -> bool:
+        v = C.c_int32()
+        _check(lib().lpp_tree_walk_status(self.handle, C.byref(v)), "lpp_tree_walk_status")
+        return bool(v.value)
+
+    def walk_reset(self, stream=None) -> None:
+        _check(lib().lpp_tree_walk_reset(self.handle, _stream(stream)), "lpp_tree_walk_reset")
+
+    def set_walk_patience(self, rounds: int) -> None:
+        _check(lib().lpp_tree_set_walk_patience(self.handle, rounds), "lpp_tree_set_walk_patience")
 
     def close(self):
         if getattr(self, "handle", None):

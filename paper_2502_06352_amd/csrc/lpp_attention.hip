@@ -78,11 +78,6 @@ __device__ __forceinline__ uint32_t div_rc(uint32_t n, uint32_t d, uint32_t rc) 
 __device__ __forceinline__ uint4 ld16(const uint16_t* p) {
   return *reinterpret_cast<const uint4*>(p);
 }
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-}
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round to nearest even (hardware convert)
   const bf16x2 v = {(__bf16)lo, (__bf16)hi};
   return __builtin_bit_cast(uint32_t, v);

@@ -22,6 +22,8 @@ struct lpp_tree {
   // device copies (null for a host-only handle)
   int device = -1;
   int32_t n_cu = 256;        // compute units of that device (launch heuristics)
+  int32_t clock_khz = 2400000;  // its shader clock
+  int32_t walk_patience = 1 << 19;   // rounds the resident-grid walk waits for the other rows (lpp_tree_set_walk_patience)
   int32_t* d_child_ptr = nullptr;  // [M + 1]
   int32_t* d_child_idx = nullptr;  // [max(N, 1)]
   uint64_t* d_anc = nullptr;       // [M * words]
@@ -44,6 +46,15 @@ struct lpp_tree {
       return LPP_EHIP;                         \
     }                                          \
   } while (0)
+
+#ifdef __HIPCC__
+// Orders the LDS traffic of one wave (no other wave is waited for).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+#endif
 
 static inline size_t lpp_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -24,6 +24,8 @@
 
 #include <type_traits>
 
+#include <atomic>
+
 #include "lpp_internal.h"
 
 namespace {
@@ -256,11 +258,6 @@ __device__ __forceinline__ double key_value(uint64_t K) {
   return __longlong_as_double((long long)u);
 }
 
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-}
 
 // Rank of each of the n entries of (skey, sidx) in the order (key desc, idx asc), without a
 // comparison sort: the keys are spread over NB buckets by a monotone map of their value
@@ -599,12 +596,12 @@ extern "C" int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, in
   const size_t sortb = (size_t)P * 6;
   const size_t lds = (size_t)P * 12 + (size_t)L.DP * 12 + (stage > sortb ? stage : sortb);
   if (lds > 150 * 1024) return LPP_EUNSUPPORTED;
-  static size_t attr_lds[2] = {0, 0};
+  static std::atomic<size_t> raised[2];   // (zero-initialised) largest dynamic LDS size enabled so far
   const void* fn = CH == 16 ? reinterpret_cast<const void*>(knn_rank_kernel<16>)
                             : reinterpret_cast<const void*>(knn_rank_kernel<32>);
-  if (lds > attr_lds[CH == 32]) {
+  if (lds > raised[CH == 32].load(std::memory_order_relaxed)) {
     LPP_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_lds[CH == 32] = lds;
+    raised[CH == 32].store(lds, std::memory_order_relaxed);
   }
   if (CH == 16)
     hipLaunchKernelGGL(knn_rank_kernel<16>, dim3((unsigned)V), dim3(kRankThreads), lds, s, a, P);

@@ -78,6 +78,8 @@ extern "C" int32_t lpp_tree_create(const int32_t* parent_host, int32_t M, lpp_tr
     int v = 0;
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, t->device) != hipSuccess) return fail();
     if (v > 0) t->n_cu = v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeClockRate, t->device) != hipSuccess) return fail();
+    if (v > 0) t->clock_khz = v;
   }
   size_t b_ptr = sizeof(int32_t) * (M + 1), b_idx = sizeof(int32_t) * t->child_idx.size(),
          b_anc = sizeof(uint64_t) * t->anc.size();
@@ -116,5 +118,37 @@ extern "C" int32_t lpp_tree_info(const lpp_tree* t, int32_t* M, int32_t* depth, 
   if (depth) *depth = t->depth;
   if (n_parents) *n_parents = t->n_parents;
   if (max_children) *max_children = t->max_children;
+  return LPP_OK;
+}
+
+// ---- state of the walk done by a resident block (lpp_relaxed_verify when B * M blocks fit the device)
+namespace {
+__global__ void mail_reset_kernel(int32_t* mail) {
+  for (int i = threadIdx.x; i < 2 * LPP_MAX_ROWS; i += blockDim.x) mail[i] = -1;
+  if (threadIdx.x == 0) mail[2 * LPP_MAX_ROWS] = 0;
+}
+}  // namespace
+
+extern "C" int32_t lpp_tree_set_walk_patience(lpp_tree* t, int32_t rounds) {
+  if (!t || rounds < -1) return LPP_EINVAL;
+  t->walk_patience = rounds > (1 << 19) ? (1 << 19) : rounds;
+  return LPP_OK;
+}
+
+extern "C" int32_t lpp_tree_walk_status(const lpp_tree* t, int32_t* gave_up) {
+  if (!t || !gave_up) return LPP_EINVAL;
+  *gave_up = 0;
+  if (!t->d_mail) return LPP_EHIP;
+  int32_t flag = 0;
+  LPP_HIP_TRY(hipMemcpy(&flag, t->d_mail + 2 * LPP_MAX_ROWS, sizeof(int32_t), hipMemcpyDeviceToHost));
+  *gave_up = flag != 0;
+  return LPP_OK;
+}
+
+extern "C" int32_t lpp_tree_walk_reset(lpp_tree* t, void* stream) {
+  if (!t) return LPP_EINVAL;
+  if (!t->d_mail) return LPP_EHIP;
+  hipLaunchKernelGGL(mail_reset_kernel, dim3(1), dim3(256), 0, reinterpret_cast<hipStream_t>(stream), t->d_mail);
+  LPP_HIP_TRY(hipGetLastError());
   return LPP_OK;
 }

@@ -42,6 +42,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 
 #include "lpp_internal.h"
@@ -51,17 +52,6 @@ namespace {
 constexpr int kMaxStage = 8;       // neighbour lists of the first children kept in LDS
 constexpr int kStageSmall = 4;     // ... when two rows per compute unit have to fit
 constexpr float kLog2e = 1.44269504088896340736f;
-
-// Build with -DLPP_VERIFY_TIMESTAMPS to record per-block phase times (100 MHz counter)
-// behind the workspace the caller passes; off in the product build.
-#ifdef LPP_VERIFY_TIMESTAMPS
-#define LPP_TS(i)                                                                                   \
-  do {                                                                                              \
-    if (threadIdx.x == 0) a.ts[(int64_t)blockIdx.x * 32 + (i)] = __builtin_amdgcn_s_memrealtime(); \
-  } while (0)
-#else
-#define LPP_TS(i) do { } while (0)
-#endif
 
 // By-value kernel argument, indexed by a wave-uniform value only (scalar loads).  Entry i
 // describes the row handled by blocks [i B, (i+1) B): rows are sorted by descending number of
@@ -105,9 +95,6 @@ struct VerifyArgs {
   int32_t spin_limit;     // (whole grid resident) how often the walking block asks for the other rows' words
   const int32_t* child_idx;   // [N] children of all rows, grouped by parent (read only if !consecutive)
   int32_t consecutive;    // every row's children are consecutive rows
-#ifdef LPP_VERIFY_TIMESTAMPS
-  unsigned long long* ts; // [blocks][32]
-#endif
 };
 
 // ---- wave64 primitives on DPP (row shifts, row broadcasts)
@@ -181,11 +168,6 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-}
 
 // exp(x - m) as exp2(x * log2(e) + m2), m2 = -m * log2(e): one FMA and the hardware exp2.
 __device__ __forceinline__ float exp2_fma(float x, float m2) {
@@ -216,6 +198,33 @@ __device__ __forceinline__ float4 mask_logits4(float4 v, int e0, int V) {
                      e0 + 3 < V ? v.w : ninf);
 }
 
+// The tail both walks share: wd[q] = parent << 1 | decision of row lane + 64 q (0 for rows that do
+// not exist).  Children are tried in ascending row index, so the child a row hands over to is its
+// lowest accepted one: next[parent] = min over accepted children, then one lane follows next[]
+// from the root.  Returns (to lane 0) the row the path ends on.
+__device__ __forceinline__ int follow_accepted(const int (&wd)[LPP_MAX_ROWS / 64], int M, int depth, int lane, int* s_next,
+                                               int32_t* accept_len, int32_t* path) {
+#pragma unroll
+  for (int q = 0; q < LPP_MAX_ROWS / 64; ++q) {
+    const int i = lane + 64 * q;
+    if (i >= 1 && i < M && (wd[q] & 1)) atomicMin(&s_next[wd[q] >> 1], i);
+  }
+  wave_lds_sync();
+  int cur = 0;
+  if (lane == 0) {
+    int n = 0;
+    while (n < depth) {
+      const int nxt = s_next[cur];
+      if (nxt == INT_MAX) break;
+      path[n++] = nxt;
+      cur = nxt;
+    }
+    for (int i = n; i < depth; ++i) path[i] = -1;
+    *accept_len = n;
+  }
+  return cur;
+}
+
 // Follow the first accepted child per level from the root (App. A.2: accepted
 // tokens are kept, everything after the first rejection is discarded).  One wave.
 // word[i] = parent(i) << 1 | decision(i) as the row kernels recorded it; s_next is M ints
@@ -235,29 +244,9 @@ __device__ __forceinline__ void walk_wave(const int32_t* word, const int32_t* fi
       s_next[i] = INT_MAX;
     }
   }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-#pragma unroll
-  for (int q = 0; q < LPP_MAX_ROWS / 64; ++q) {
-    const int i = lane + 64 * q;
-    if (i >= 1 && i < M && (wd[q] & 1)) atomicMin(&s_next[wd[q] >> 1], i);
-  }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-  if (lane == 0) {
-    int cur = 0, n = 0;
-    while (n < depth) {
-      const int nxt = s_next[cur];
-      if (nxt == INT_MAX) break;
-      path[n++] = nxt;
-      cur = nxt;
-    }
-    for (int i = n; i < depth; ++i) path[i] = -1;
-    *accept_len = n;
-    *final_token = s_fin[cur];
-  }
+  wave_lds_sync();
+  const int cur = follow_accepted(wd, M, depth, lane, s_next, accept_len, path);
+  if (lane == 0) *final_token = s_fin[cur];
 }
 
 // Walk of one item when the whole grid is resident at once (one wave of the block that walks).
@@ -336,27 +325,9 @@ __device__ __forceinline__ void collect_and_walk(MailRound r, int32_t* mail, int
       s_next[i] = INT_MAX;
     }
   }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-#pragma unroll
-  for (int q = 0; q < Q; ++q) {
-    const int i = lane + 64 * q;
-    if (i >= 1 && i < M && (wd[q] & 1)) atomicMin(&s_next[wd[q] >> 1], i);
-  }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+  wave_lds_sync();
+  const int cur = follow_accepted(wd, M, depth, lane, s_next, accept_len, path);
   if (lane == 0) {
-    int cur = 0, n = 0;
-    while (n < depth) {
-      const int nxt = s_next[cur];
-      if (nxt == INT_MAX) break;
-      path[n++] = nxt;
-      cur = nxt;
-    }
-    for (int i = n; i < depth; ++i) path[i] = -1;
-    *accept_len = n;
     if (cur != P) *final_token = s_fin[cur];      // (ended on this block's own row: its draw is with wave 0)
     *s_end = cur;
   }
@@ -432,7 +403,6 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  LPP_TS(0);
   const int b = blockIdx.x % a.B;
   const uint32_t ri = tt.rowinfo[blockIdx.x / a.B];
   const int P = ri & 255u;
@@ -718,7 +688,6 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
   md = wave_max(md);
   if (lane == 0) { s_max[0][w] = mt; s_max[1][w] = md; }
   lds_barrier();
-  LPP_TS(2);
   mt = combine_max<NW>(s_max[0], lane);
   md = combine_max<NW>(s_max[1], lane);
   if (mt == -INFINITY) mt = 0.f;
@@ -763,7 +732,6 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
       }
     }
   lds_barrier();
-  LPP_TS(3);
   st = combine_sum<NW>(s_sum[0], lane);
   sd = combine_sum<NW>(s_sum[1], lane);
   float rs = st > 0.f ? 1.0f / st : 0.f;           // r_true = r_lds * rs
@@ -932,9 +900,7 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
     if (skip_rule) {
       if (tid == 0) { s_jstar = 1 + cnt_sk; s_mass = cum_sk; r_lds[t] = cum_sk; }
     } else if (!found && tid == 0) { s_jstar = k; s_mass = carry; r_lds[t] = carry; }
-    if (ci < 8) LPP_TS(4 + 3 * ci);
     lds_barrier();
-    if (ci < 8) LPP_TS(5 + 3 * ci);
     // p(x^) with distinct siblings: the drafter's probability of the token in what is left of p
     float pt = 0.f;
     if (ALT) {
@@ -984,7 +950,6 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
     z = wave_sum(z);
     if (lane == 0) s_z[ci & 1][w] = z;
     lds_barrier();
-    if (ci < 8) LPP_TS(6 + 3 * ci);
     z = combine_sum<NW, STAG>(s_z[ci & 1], lane);
     rt_nx = r_lds[t_nx];
     v0_nx = r_lds[pk_nx & 0xFFFFu];
@@ -1049,7 +1014,6 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
     if (lane < NCH) s_cell[lane * NW + w] = mine;
   }
   for (int i = NC + tid; i < 64 * CPL; i += NT) s_cell[i] = 0.f;
-  LPP_TS(28);
   if (w != 0 && nchild > 64 * w) {
     // (rare: more than 64 children)  this wave's stores have to be complete before wave 0 takes
     // the row's ticket, which it does after the barrier below
@@ -1133,7 +1097,6 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
     x = __builtin_amdgcn_readlane(tb + 4 * lane + e, l);
   }
   x = min(x, V - 1);
-  LPP_TS(29);
   write_children(0, min(nchild, 64));
   int ticket = 0;
   if (lane == 0) {
@@ -1162,7 +1125,6 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
     if (walker) {
       lds_barrier();         // the walk is done
       if (lane == 0 && s_mail[3 * LPP_MAX_ROWS] == P) a.final_token[b] = x;
-      LPP_TS(30);
     }
     return;
   }
@@ -1175,7 +1137,6 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
   walk_wave(a.ws_decision + nodebase, a.ws_final + nodebase, a.M, a.depth, lane, s_walk, s_walk + a.M,
             a.accept_len + b, a.path + (int64_t)b * a.depth, a.final_token + b);
   if (lane == 0) __hip_atomic_store(&a.counters[b], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);    // ready for the next call
-  LPP_TS(30);
 }
 
 // Stand-alone walk for batches larger than the counter array: one wave per item.
@@ -1189,7 +1150,7 @@ __global__ __launch_bounds__(64) void walk_kernel(VerifyArgs a) {
 
 template <int NT, int NCH, bool ALIGNED, bool FRONT, bool ALT, bool STAG>
 int32_t launch_rows(const VerifyArgs& a_in, const TreeTab& tt, hipStream_t stream) {
-  static size_t attr_lds = 0;   // largest dynamic LDS size this instantiation was enabled for
+  static std::atomic<size_t> raised{0};   // largest dynamic LDS size this instantiation was enabled for
   VerifyArgs a = a_in;
   auto lds_for = [](int nstage) {
     return ((size_t)NT * NCH * 4 + 4) * sizeof(float) + (size_t)nstage * NT * sizeof(uint32_t) +
@@ -1199,10 +1160,10 @@ int32_t launch_rows(const VerifyArgs& a_in, const TreeTab& tt, hipStream_t strea
   while (a.nstage > 0 && lds_for(a.nstage) > 152 * 1024) --a.nstage;
   const size_t lds = lds_for(a.nstage);
   auto kern = verify_rows_kernel<NT, NCH, ALIGNED, FRONT, ALT, STAG>;
-  if (lds > attr_lds) {
+  if (lds > raised.load(std::memory_order_relaxed)) {
     LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_lds = lds;
+    raised.store(lds, std::memory_order_relaxed);
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.M)), dim3(NT), lds, stream, a, tt);
   LPP_HIP_TRY(hipGetLastError());
@@ -1261,9 +1222,6 @@ int32_t relaxed_verify_impl(int32_t additive, int32_t skip, int32_t norepl, bool
   bool fused_walk = B <= LPP_COUNTER_SLOTS;
   a.counters = fused_walk ? tree->d_counters : nullptr;
   a.spin_limit = 0;
-#ifdef LPP_VERIFY_TIMESTAMPS
-  a.ts = reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(ws) + need);
-#endif
 
   a.child_idx = tree->d_child_idx;
   a.consecutive = tree->consecutive_children ? 1 : 0;
@@ -1285,20 +1243,16 @@ int32_t relaxed_verify_impl(int32_t additive, int32_t skip, int32_t norepl, bool
   // push back.
   a.n_parents = tree->n_parents;
   a.wait_parent = a.wait_leaf = 0;
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0, v = 0;
-    LPP_HIP_TRY(hipGetDevice(&dev));
-    LPP_HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
-    n_cu = std::max(v, 1);
-  }
-  const bool stag = (int64_t)B * tree->M <= std::min(n_cu, LPP_MAX_ROWS) && !front && !alt && tree->d_mail != nullptr;
+  // (The walk by a resident block assumes that all B * M blocks of the launch are on the device at
+  // once: one block per compute unit, the device not shared with other work meanwhile.  If that
+  // does not hold the walk may give up, which lpp_tree_walk_status reports.)
+  const bool stag = (int64_t)B * tree->M <= std::min<int32_t>(tree->n_cu, LPP_MAX_ROWS) && !front && !alt && tree->d_mail != nullptr;
   if (stag) {
-    double stagger = 0.8;             // of the time the memory system needs for the bytes asked for ahead of a row (measured best: 0.7 .. 0.9)
-    if (const char* e = getenv("LPP_VERIFY_STAGGER")) stagger = atof(e);
-    if (!(stagger >= 0.0 && stagger <= 4.0)) stagger = 0.8;
-    // one logit row of every item at 5 TB/s, in 1/256 of the kernel's sleep unit (1024 clocks at 2.4 GHz)
-    const double ticks_per_row = (double)B * V * 4.0 / 5.0e12 * 2.4e9 / 1024.0 * 256.0 * stagger;
+    // Tuned on MI355X (256 compute units): a row waits for 0.8 of the time the memory system needs,
+    // at kStaggerBytesPerSecond, for the bytes asked for ahead of it (measured best: 0.7 .. 0.9).
+    constexpr double kStagger = 0.8, kStaggerBytesPerSecond = 5.0e12;
+    // one logit row of every item, in 1/256 of the kernel's sleep unit (1024 clocks)
+    const double ticks_per_row = (double)B * V * 4.0 / kStaggerBytesPerSecond * (tree->clock_khz * 1.0e3) / 1024.0 * 256.0 * kStagger;
     a.wait_parent = (int32_t)(2.0 * ticks_per_row);
     a.wait_leaf = (int32_t)ticks_per_row;
     // the other rows' words reach the walking block through the tree's mail words, not the workspace
@@ -1307,8 +1261,7 @@ int32_t relaxed_verify_impl(int32_t additive, int32_t skip, int32_t norepl, bool
     a.counters = nullptr;
     fused_walk = true;
     // about 0.5 us a round: a quarter of a second before the walk gives up (see collect_and_walk)
-    a.spin_limit = 1 << 19;
-    if (const char* e = getenv("LPP_VERIFY_SPIN_LIMIT")) a.spin_limit = std::max(-1, std::min(atoi(e), 1 << 19));
+    a.spin_limit = tree->walk_patience;
   }
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);

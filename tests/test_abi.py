@@ -43,6 +43,21 @@ def test_every_declared_function_is_exported(L):
     assert L.lpp_strerror(99).decode() == "unknown status"
 
 
+def test_walk_state_calls_validate(L):
+    t = lpp.Tree([-1, 0, 0, 1])
+    v = C.c_int32(7)
+    assert L.lpp_tree_walk_status(None, C.byref(v)) == lpp.LPP_EINVAL
+    assert L.lpp_tree_walk_status(t.handle, None) == lpp.LPP_EINVAL
+    assert L.lpp_tree_walk_reset(None, None) == lpp.LPP_EINVAL
+    assert L.lpp_tree_set_walk_patience(None, 5) == lpp.LPP_EINVAL
+    assert L.lpp_tree_set_walk_patience(t.handle, -2) == lpp.LPP_EINVAL
+    assert L.lpp_tree_set_walk_patience(t.handle, 1 << 30) == lpp.LPP_OK      # (capped)
+    import torch
+    if not torch.cuda.is_available():                                          # host-only handle
+        assert L.lpp_tree_walk_status(t.handle, C.byref(v)) == lpp.LPP_EHIP and v.value == 0
+        assert L.lpp_tree_walk_reset(t.handle, None) == lpp.LPP_EHIP
+
+
 def _create(L, parent):
     parent = np.asarray(parent, dtype=np.int32)
     h = C.c_void_p()

@@ -147,24 +147,31 @@ def test_verify_walk_by_a_row_other_than_the_root_and_repeated_calls():
         assert rep["nodes"] > 0
 
 
-def test_verify_walk_that_gives_up_is_loud(monkeypatch):
+def test_verify_walk_that_gives_up_is_loud_and_can_be_reset():
     # The bounded wait of the walking block is made to run out from the host (no kernel hangs or
     # faults: the block just does not look at the results).  The call must say so in its outputs,
-    # the handle must stay marked, and a new handle must work.
+    # the handle must stay marked and say so when asked, and a reset must make it good again.
     cfg = CONFIGS[1]
     parent = static_tree(cfg.branching, cfg.N)
     x = make_verify_inputs(cfg, parent, rho=0.8)
     neigh = sparse_neighbour_table(make_codebook(cfg), cfg.k, x["tokens"][:, 1:], cfg.V)
     tree = lpp.Tree(parent)
-    monkeypatch.setenv("LPP_VERIFY_SPIN_LIMIT", "-1")
+    assert not tree.walk_gave_up()
+    tree.set_walk_patience(-1)
     got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam, want_all=False)
     assert np.all(got["accept_len"] == -1) and np.all(got["final_token"] == -1) and np.all(got["path"] == -1)
-    monkeypatch.delenv("LPP_VERIFY_SPIN_LIMIT")
+    assert tree.walk_gave_up()
+    tree.set_walk_patience(1 << 19)
     got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam, want_all=False)
     assert np.all(got["accept_len"] == -1) and np.all(got["final_token"] == -1)
-    fresh = lpp.Tree(parent)
-    got = run_verify(fresh, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam)
-    compare_verify(parent, x, neigh, cfg.V, cfg.vocab_offset, cfg.k, cfg.lam, got)
+    tree.walk_reset()
+    torch.cuda.synchronize()
+    assert not tree.walk_gave_up()
+    for _ in range(2):
+        got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam)
+        compare_verify(parent, x, neigh, cfg.V, cfg.vocab_offset, cfg.k, cfg.lam, got)
+    with pytest.raises(lpp.LppError):
+        tree.set_walk_patience(-2)
 
 
 @pytest.mark.parametrize("B,parent", [(120, [-1, 0]), (85, [-1, 0, 0]), (64, [-1, 0, 1, 2])])
