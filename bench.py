@@ -22,9 +22,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 # HBM bytes per launch (fetched + written) per workload config from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# runs of this script (summaries under profiles/), scaled by the same counters' reading for a copy
-# of known size; a kernel that is not listed has not been measured (reported as null).
-TRAFFIC = {3: {"tree_attention": 29.11e6, "relaxed_verify": 30.20e6}}
+# runs of this script, scaled by the same counters' reading for a copy of known size (the summary and
+# the commands: profiles/verify_attention_hbm_bytes_all_configs.txt).  They hold for the plain step
+# (one layer, multi-head, no front end, default options); otherwise the bench reports null.
+TRAFFIC = {1: {"tree_attention": 4.49e6, "relaxed_verify": 0.35e6},
+           2: {"tree_attention": 5.13e6, "relaxed_verify": 3.42e6},
+           3: {"tree_attention": 29.13e6, "relaxed_verify": 30.20e6},
+           4: {"tree_attention": 50.38e6, "relaxed_verify": 4.17e6},
+           5: {"tree_attention": 450.22e6, "relaxed_verify": 256.40e6}}
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
@@ -45,6 +50,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload config 1..5 (3 = the metric's shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rotate", action="store_true", help="one replica only (cache-resident inputs)")
+    ap.add_argument("--replicas", type=int, default=0,
+                    help="input replicas to rotate over (default: enough for R x working set >= 512 MB, at most 64)")
     ap.add_argument("--no-cached", action="store_true",
                     help="leave out the cache-resident pass (so that a kernel trace of this run holds HBM-resident "
                          "calls only)")
@@ -151,6 +158,8 @@ def main():
     step_bytes = L * attn_bytes + verify_bytes
     R = 1 if args.no_rotate else max(2, int(np.ceil(512e6 / step_bytes)))
     R = min(R, 64)
+    if args.replicas > 0 and not args.no_rotate:
+        R = args.replicas
     reps = []
     for r in range(R):
         d = {}

@@ -42,12 +42,16 @@ def test_attention_parity_configs(idx):
     _check(cfg, parent, att, got)
 
 
-def test_attention_parity_stress_full_size_sampled_heads():
+def test_attention_parity_stress_full_size():
+    # config 5 at its full size: every head of three batch items (the first, one in the middle, the
+    # last) and one head of every other item
     cfg = CONFIGS[5]
     parent = static_tree(cfg.branching, cfg.N)
     att = make_attention_inputs(cfg)
     got = run_attention(lpp.Tree(parent), att, cfg)
-    _check(cfg, parent, att, got, pairs=[(0, 0), (3, 17), (9, 5), (15, 23)])
+    pairs = [(b, h) for b in (0, 7, cfg.B - 1) for h in range(cfg.H)]
+    pairs += [(b, (5 * b + 3) % cfg.H) for b in range(cfg.B) if b not in (0, 7, cfg.B - 1)]
+    _check(cfg, parent, att, got, pairs=pairs)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])

@@ -27,8 +27,29 @@ def test_knn_tiny_full():
     _check_rows(E, cfg.k, got, np.arange(cfg.V))
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4])
-def test_knn_full_size_sampled_rows(idx):
+def _check_every_row(E, k, got, block=512, workers=8):
+    """The brute-force oracle for every row, in row blocks spread over a few worker processes
+    (spawned: they import the oracle only)."""
+    import multiprocessing as mp
+    from concurrent.futures import ProcessPoolExecutor
+    from oracle_pool import oracle_rows
+    V = E.shape[0]
+    jobs = [(E, k, lo, min(lo + block, V)) for lo in range(0, V, block)]
+    bad_rows = 0
+    first = None
+    with ProcessPoolExecutor(max_workers=workers, mp_context=mp.get_context("spawn")) as pool:
+        for lo, want in pool.map(oracle_rows, jobs):
+            bad = np.flatnonzero((got[lo:lo + len(want)] != want).any(axis=1))
+            bad_rows += bad.size
+            if bad.size and first is None:
+                first = (lo + int(bad[0]), got[lo + bad[0]][:12], want[bad[0]][:12])
+    assert bad_rows == 0, f"{bad_rows} of {V} rows differ; first {first}"
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+def test_knn_full_size_every_row(idx):
+    # every row of the table at the full size of every workload config (config 5 has the shape
+    # of config 3 and a codebook of its own)
     cfg = CONFIGS[idx]
     E = make_codebook(cfg)
     got = run_knn(E, cfg.k)
@@ -37,9 +58,7 @@ def test_knn_full_size_sampled_rows(idx):
     # every row is a set of k distinct codes
     srt = np.sort(got, axis=1)
     assert np.all(srt[:, 1:] != srt[:, :-1])
-    rows = np.random.default_rng(idx).choice(cfg.V, size=192, replace=False)
-    rows = np.concatenate([[0, cfg.V - 1], rows])
-    _check_rows(E, cfg.k, got, rows)
+    _check_every_row(E, cfg.k, got)
 
 
 def test_knn_ragged_shapes():
