@@ -238,6 +238,8 @@ int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_logits,
  * results bit for bit -- is as for lpp_relaxed_verify.  All calls on one GPU share that array and
  * it keeps the last call's contents (every word a call reads it has written before): two calls
  * whose kernels may overlap on one GPU (different streams, different threads) race; order them.
+ * The first call on a device looks the array's address up (no stream work): make it outside a
+ * graph capture; later calls may be captured.
  * Errors: as lpp_relaxed_verify (no LPP_ENOWORKSPACE), plus LPP_EUNSUPPORTED when
  * B * M > LPP_STATIC_MAX_NODES or the device index is 64 or more.
  */

@@ -129,7 +129,7 @@ struct Stage {
 // rows [rw NT 16, (rw + 1) NT 16).  The RW waves that share a key group load it independently; the
 // second read is served by the compute unit's own cache.
 template <int DH, int NT, int RW, int KW>
-__global__ __launch_bounds__(RW * KW * 64) void tree_attn_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(RW * KW * 64, (RW * KW == 4 && DH == 64 ? 3 : 1)) void tree_attn_bf16_kernel(AttnArgs a) {
   static_assert(RW == 1, "a block is one row range; its waves split the keys");
   constexpr int W = RW * KW;
   constexpr int KS = DH / 32;        // contraction steps of Q K^T
@@ -724,10 +724,14 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh, int l
     p.msplits = (p.mtiles + 4) / 5;
     p.nt = (p.mtiles + p.msplits - 1) / p.msplits;
   }
-  p.kw = 8;
   const int G = (S + 31) / 32 + (tree->M + 31) / 32;
   const int64_t blocks_bh = (int64_t)B * H * p.msplits * std::max(1, std::min(layers, kLayersPerLaunch));
-  int ns = (int)std::min<int64_t>(tree->n_cu / blocks_bh, 1 << 20);   // one block of 8 waves per compute unit
+  // Blocks of 8 waves, one per compute unit -- unless the launch has more blocks than compute units
+  // (several layers) and a wave of a 4-wave block still has two groups or more: then two or three
+  // such blocks share a compute unit and cover each other's fixed latencies (first bytes, in-block
+  // merge, write-out), which the waves of one block, in step with each other, cannot.
+  p.kw = (p.nt == 2 && blocks_bh > (int64_t)tree->n_cu && G >= 8) ? 4 : 8;
+  int ns = (int)std::min<int64_t>(tree->n_cu / blocks_bh, 1 << 20);   // key splits only while a compute unit would idle
   const int max_ns = G / (2 * p.kw);              // at least two key groups per wave
   if (ns > max_ns) ns = max_ns;
   if (ns < 1) ns = 1;
@@ -740,20 +744,11 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh, int l
   return p;
 }
 
-// Raises the dynamic LDS limit of a kernel when a launch needs more than it was raised to so far.
-int32_t ensure_lds(const void* kern, std::atomic<size_t>& raised, size_t lds) {
-  if (lds > raised.load(std::memory_order_relaxed)) {
-    LPP_HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    raised.store(lds, std::memory_order_relaxed);
-  }
-  return LPP_OK;
-}
-
 template <int DH, int NT, int RW, int KW>
 int32_t launch_bf16(const AttnArgs& a, const AttnPlan& p, hipStream_t s) {
-  static std::atomic<size_t> raised{48 * 1024};
+  static LppLdsLimit limit;
   auto kern = tree_attn_bf16_kernel<DH, NT, RW, KW>;
-  const int32_t st = ensure_lds(reinterpret_cast<const void*>(kern), raised, p.lds);
+  const int32_t st = lpp_ensure_lds(reinterpret_cast<const void*>(kern), limit, p.lds, 48 * 1024);
   if (st != LPP_OK) return st;
   hipLaunchKernelGGL(kern, dim3(a.blocks_per_layer * (unsigned)a.n_layers), dim3(RW * KW * 64), p.lds, s, a);
   LPP_HIP_TRY(hipGetLastError());
@@ -824,10 +819,10 @@ int32_t tree_attention_impl(const lpp_tree* tree, int32_t dtype, int32_t out_dty
       a.seq_len = seq_len; a.anc = tree->d_anc;
       a.B = B; a.H = H; a.S = S; a.M = tree->M; a.words = tree->words; a.Dh = Dh; a.scale = scale;
       a.gq = H / Hkv; a.out_bf16 = out_dtype == LPP_BF16;
-      static std::atomic<size_t> raised{48 * 1024};
+      static LppLdsLimit limit;
       const size_t lds = (size_t)(S + tree->M) * sizeof(float);
       if (lds > 144 * 1024) return LPP_EUNSUPPORTED;     // the scores of one row are kept in LDS
-      const int32_t st = ensure_lds(reinterpret_cast<const void*>(tree_attn_f32_kernel), raised, lds);
+      const int32_t st = lpp_ensure_lds(reinterpret_cast<const void*>(tree_attn_f32_kernel), limit, lds, 48 * 1024);
       if (st != LPP_OK) return st;
       hipLaunchKernelGGL(tree_attn_f32_kernel, dim3((unsigned)tree->M, (unsigned)(B * H), (unsigned)nl), dim3(256), lds,
                          s, a);
@@ -871,13 +866,13 @@ int32_t tree_attention_impl(const lpp_tree* tree, int32_t dtype, int32_t out_dty
     int32_t st = LPP_EUNSUPPORTED;
     if (Dh == 64) {
       if (p.nt == 1) st = launch_bf16<64, 1, 1, 8>(a, p, s);
-      else if (p.nt == 2) st = launch_bf16<64, 2, 1, 8>(a, p, s);
+      else if (p.nt == 2) st = p.kw == 4 ? launch_bf16<64, 2, 1, 4>(a, p, s) : launch_bf16<64, 2, 1, 8>(a, p, s);
       else if (p.nt == 3) st = launch_bf16<64, 3, 1, 8>(a, p, s);
       else if (p.nt == 4) st = launch_bf16<64, 4, 1, 8>(a, p, s);
       else st = launch_bf16<64, 5, 1, 8>(a, p, s);
     } else {
       if (p.nt == 1) st = launch_bf16<128, 1, 1, 8>(a, p, s);
-      else if (p.nt == 2) st = launch_bf16<128, 2, 1, 8>(a, p, s);
+      else if (p.nt == 2) st = p.kw == 4 ? launch_bf16<128, 2, 1, 4>(a, p, s) : launch_bf16<128, 2, 1, 8>(a, p, s);
     }
     if (st != LPP_OK) return st;
   }

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include <vector>
 
 #include "lpp.h"
@@ -46,6 +47,25 @@ struct lpp_tree {
       return LPP_EHIP;                         \
     }                                          \
   } while (0)
+
+// The largest dynamic LDS size a kernel has been enabled for so far, per device: the attribute
+// (hipFuncAttributeMaxDynamicSharedMemorySize) belongs to one device's copy of the kernel.  One
+// such cache per kernel, zero-initialised; `floor` is what a kernel may use without asking.
+constexpr int kLppMaxDevices = 64;
+struct LppLdsLimit {
+  std::atomic<size_t> raised[kLppMaxDevices];
+};
+inline int32_t lpp_ensure_lds(const void* kern, LppLdsLimit& lim, size_t lds, size_t floor = 0) {
+  if (lds <= floor) return LPP_OK;
+  int dev = -1;
+  LPP_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kLppMaxDevices) return LPP_EUNSUPPORTED;
+  if (lds > lim.raised[dev].load(std::memory_order_relaxed)) {
+    LPP_HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    lim.raised[dev].store(lds, std::memory_order_relaxed);
+  }
+  return LPP_OK;
+}
 
 #ifdef __HIPCC__
 // Orders the LDS traffic of one wave (no other wave is waited for).

@@ -531,14 +531,11 @@ KnnLayout knn_layout(int32_t V, int32_t D, int32_t k) {
 
 template <int NS4>
 int32_t launch_select(const KnnArgs& a, hipStream_t s) {
-  static bool attr_set = false;
   const size_t lds = (size_t)kSelRows * (kBins / 2) * sizeof(uint32_t);
   auto kern = knn_select_kernel<NS4>;
-  if (!attr_set) {
-    LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  static LppLdsLimit limit;
+  const int32_t st = lpp_ensure_lds(reinterpret_cast<const void*>(kern), limit, lds);
+  if (st != LPP_OK) return st;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.Vp / kSelRows)), dim3(kSelWaves * 64), lds, s, a);
   LPP_HIP_TRY(hipGetLastError());
   return LPP_OK;
@@ -596,13 +593,11 @@ extern "C" int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, in
   const size_t sortb = (size_t)P * 6;
   const size_t lds = (size_t)P * 12 + (size_t)L.DP * 12 + (stage > sortb ? stage : sortb);
   if (lds > 150 * 1024) return LPP_EUNSUPPORTED;
-  static std::atomic<size_t> raised[2];   // (zero-initialised) largest dynamic LDS size enabled so far
+  static LppLdsLimit limit[2];   // (zero-initialised) one per kernel
   const void* fn = CH == 16 ? reinterpret_cast<const void*>(knn_rank_kernel<16>)
                             : reinterpret_cast<const void*>(knn_rank_kernel<32>);
-  if (lds > raised[CH == 32].load(std::memory_order_relaxed)) {
-    LPP_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    raised[CH == 32].store(lds, std::memory_order_relaxed);
-  }
+  const int32_t st = lpp_ensure_lds(fn, limit[CH == 32], lds);
+  if (st != LPP_OK) return st;
   if (CH == 16)
     hipLaunchKernelGGL(knn_rank_kernel<16>, dim3((unsigned)V), dim3(kRankThreads), lds, s, a, P);
   else

@@ -1150,7 +1150,7 @@ __global__ __launch_bounds__(64) void walk_kernel(VerifyArgs a) {
 
 template <int NT, int NCH, bool ALIGNED, bool FRONT, bool ALT, bool STAG>
 int32_t launch_rows(const VerifyArgs& a_in, const TreeTab& tt, hipStream_t stream) {
-  static std::atomic<size_t> raised{0};   // largest dynamic LDS size this instantiation was enabled for
+  static LppLdsLimit limit;   // (zero-initialised) one per instantiation
   VerifyArgs a = a_in;
   auto lds_for = [](int nstage) {
     return ((size_t)NT * NCH * 4 + 4) * sizeof(float) + (size_t)nstage * NT * sizeof(uint32_t) +
@@ -1160,11 +1160,8 @@ int32_t launch_rows(const VerifyArgs& a_in, const TreeTab& tt, hipStream_t strea
   while (a.nstage > 0 && lds_for(a.nstage) > 152 * 1024) --a.nstage;
   const size_t lds = lds_for(a.nstage);
   auto kern = verify_rows_kernel<NT, NCH, ALIGNED, FRONT, ALT, STAG>;
-  if (lds > raised.load(std::memory_order_relaxed)) {
-    LPP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    raised.store(lds, std::memory_order_relaxed);
-  }
+  const int32_t st = lpp_ensure_lds(reinterpret_cast<const void*>(kern), limit, lds);
+  if (st != LPP_OK) return st;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.M)), dim3(NT), lds, stream, a, tt);
   LPP_HIP_TRY(hipGetLastError());
   return LPP_OK;
@@ -1312,15 +1309,14 @@ extern "C" int32_t lpp_relaxed_verify(const lpp_tree* tree, const float* target_
 static __device__ __align__(256) unsigned char scratch[LPP_STATIC_SCRATCH_BYTES];
 
 namespace {
-constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
-void* g_scratch_ptr[kMaxDevices] = {};
+void* g_scratch_ptr[kLppMaxDevices] = {};
 
 // Device address of `scratch` on the current device (each device holds its own copy).
 int32_t static_scratch(void** out) {
   int dev = -1;
   LPP_HIP_TRY(hipGetDevice(&dev));
-  if (dev < 0 || dev >= kMaxDevices) return LPP_EUNSUPPORTED;
+  if (dev < 0 || dev >= kLppMaxDevices) return LPP_EUNSUPPORTED;
   std::lock_guard<std::mutex> lock(g_scratch_mutex);
   if (!g_scratch_ptr[dev]) {
     void* ptr = nullptr;

@@ -48,10 +48,13 @@ def _run_layers(tree, atts, cfg, Hkv, out_dtype=lpp.LPP_F32, seq_len=None):
     return [o.float().cpu().numpy() for o in outs]
 
 
-@pytest.mark.parametrize("idx,L,Hkv", [(1, 3, 4), (2, 3, 16), (3, 3, 24), (4, 3, 32), (2, 19, 16), (3, 2, 8)])
+@pytest.mark.parametrize("idx,L,Hkv", [(1, 3, 4), (2, 3, 16), (3, 3, 24), (4, 3, 32), (2, 19, 16), (3, 2, 8),
+                                       (4, 5, 8)])
 def test_layers_parity(idx, L, Hkv):
     # cfg 2 and 4 at L = 3 split the keys of a head over several blocks (partials and counters per
-    # layer); L = 19 takes two launches; cfg 3 with 8 key/value heads shares them among query heads
+    # layer); L = 19 takes two launches; cfg 3 with 8 key/value heads shares them among query heads.
+    # Launches with more blocks than compute units run blocks of 4 waves: cfg 3 at L = 2 and 3
+    # (head size 64), cfg 4 at L = 5 (head size 128, 8 key/value heads).
     cfg = CONFIGS[idx]
     parent = static_tree(cfg.branching, cfg.N)
     tree = lpp.Tree(parent)
