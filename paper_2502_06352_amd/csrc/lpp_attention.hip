@@ -129,7 +129,7 @@ struct Stage {
 // rows [rw NT 16, (rw + 1) NT 16).  The RW waves that share a key group load it independently; the
 // second read is served by the compute unit's own cache.
 template <int DH, int NT, int RW, int KW>
-__global__ __launch_bounds__(RW * KW * 64, (RW * KW == 4 && DH == 64 ? 3 : 1)) void tree_attn_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(RW * KW * 64, (RW * KW == 4 && DH == 64 ? (NT == 2 ? 3 : 2) : 1)) void tree_attn_bf16_kernel(AttnArgs a) {
   static_assert(RW == 1, "a block is one row range; its waves split the keys");
   constexpr int W = RW * KW;
   constexpr int KS = DH / 32;        // contraction steps of Q K^T
@@ -142,8 +142,8 @@ __global__ __launch_bounds__(RW * KW * 64, (RW * KW == 4 && DH == 64 ? 3 : 1)) v
   constexpr int WROWS = NT * 16;     // rows of a wave
   constexpr int ROWS = RW * WROWS;   // rows of the block
   constexpr int OPITCH = DH + 4;     // floats per row of the merge buffer
-  // merge slots: one per wave if that fits where the V tiles were (or in 96 KB), else half as many
-  constexpr int MS = (KW * NT * 16 * (DH + 4) * 4 <= (KW * 2 * VTILE > 96 * 1024 ? KW * 2 * VTILE : 96 * 1024)) ? KW : KW / 2;
+  // merge slots: one per wave if that fits where the V tiles were (or in 12 KB per wave), else half as many
+  constexpr int MS = (KW * NT * 16 * (DH + 4) * 4 <= (KW * 2 * VTILE > KW * 12 * 1024 ? KW * 2 * VTILE : KW * 12 * 1024)) ? KW : KW / 2;
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_ticket;
 
@@ -727,10 +727,14 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh, int l
   const int G = (S + 31) / 32 + (tree->M + 31) / 32;
   const int64_t blocks_bh = (int64_t)B * H * p.msplits * std::max(1, std::min(layers, kLayersPerLaunch));
   // Blocks of 8 waves, one per compute unit -- unless the launch has more blocks than compute units
-  // (several layers) and a wave of a 4-wave block still has two groups or more: then two or three
-  // such blocks share a compute unit and cover each other's fixed latencies (first bytes, in-block
-  // merge, write-out), which the waves of one block, in step with each other, cannot.
-  p.kw = (p.nt == 2 && blocks_bh > (int64_t)tree->n_cu && G >= 8) ? 4 : 8;
+  // and a wave of a 4-wave block still has two groups or more: then two or three such blocks share
+  // a compute unit and cover each other's fixed latencies (first bytes, in-block merge, write-out)
+  // and stalls, which the waves of one block, in step with each other, cannot.  With three tiles or
+  // more per wave (two waves per SIMD either way) that pays from two rounds of blocks on.
+  p.kw = 8;
+  if (G >= 8 && ((p.nt == 2 && blocks_bh > (int64_t)tree->n_cu) ||
+                 (p.nt >= 3 && Dh == 64 && blocks_bh >= 2 * (int64_t)tree->n_cu)))
+    p.kw = 4;
   int ns = (int)std::min<int64_t>(tree->n_cu / blocks_bh, 1 << 20);   // key splits only while a compute unit would idle
   const int max_ns = G / (2 * p.kw);              // at least two key groups per wave
   if (ns > max_ns) ns = max_ns;
@@ -738,7 +742,7 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh, int l
   p.nsplit = ns;
   const int rows = p.nt * 16;
   const size_t vt = (size_t)p.kw * 2 * 32 * (Dh * 2 + 32);
-  const int ms = (size_t)p.kw * rows * (Dh + 4) * 4 <= std::max<size_t>(vt, 96 * 1024) ? p.kw : p.kw / 2;
+  const int ms = (size_t)p.kw * rows * (Dh + 4) * 4 <= std::max<size_t>(vt, (size_t)p.kw * 12 * 1024) ? p.kw : p.kw / 2;
   const size_t og = (size_t)ms * rows * (Dh + 4) * sizeof(float);
   p.lds = (vt > og ? vt : og) + (size_t)2 * (p.kw + 1) * rows * sizeof(float);
   return p;
@@ -867,9 +871,9 @@ int32_t tree_attention_impl(const lpp_tree* tree, int32_t dtype, int32_t out_dty
     if (Dh == 64) {
       if (p.nt == 1) st = launch_bf16<64, 1, 1, 8>(a, p, s);
       else if (p.nt == 2) st = p.kw == 4 ? launch_bf16<64, 2, 1, 4>(a, p, s) : launch_bf16<64, 2, 1, 8>(a, p, s);
-      else if (p.nt == 3) st = launch_bf16<64, 3, 1, 8>(a, p, s);
-      else if (p.nt == 4) st = launch_bf16<64, 4, 1, 8>(a, p, s);
-      else st = launch_bf16<64, 5, 1, 8>(a, p, s);
+      else if (p.nt == 3) st = p.kw == 4 ? launch_bf16<64, 3, 1, 4>(a, p, s) : launch_bf16<64, 3, 1, 8>(a, p, s);
+      else if (p.nt == 4) st = p.kw == 4 ? launch_bf16<64, 4, 1, 4>(a, p, s) : launch_bf16<64, 4, 1, 8>(a, p, s);
+      else st = p.kw == 4 ? launch_bf16<64, 5, 1, 4>(a, p, s) : launch_bf16<64, 5, 1, 8>(a, p, s);
     } else {
       if (p.nt == 1) st = launch_bf16<128, 1, 1, 8>(a, p, s);
       else if (p.nt == 2) st = p.kw == 4 ? launch_bf16<128, 2, 1, 4>(a, p, s) : launch_bf16<128, 2, 1, 8>(a, p, s);
