@@ -73,11 +73,14 @@ int32_t lpp_tree_info(const lpp_tree* tree, int32_t* M, int32_t* depth,
  * rows' results (see lpp_relaxed_verify).  That presumes the launch's blocks are all resident
  * together: the stream's kernel has the device to itself (no compute-unit mask, no long kernel of
  * another stream or process in the way).  If the wait ever runs out, the item's accept_len, path and
- * final_token are -1 for that call and for every later call on the handle, until it is reset:
- *   lpp_tree_walk_status   [host] gave_up = 1 if that has happened.  Copies one word back from the
- *                          device: it waits for the device (not for use inside a capture).
- *   lpp_tree_walk_reset    enqueues on `stream` the kernel that clears that state; the handle is good
- *                          again for calls ordered after it.
+ * final_token are -1 for that call, and for that call only: the rows' results carry the number of
+ * their call, so whatever arrives late is not taken for a later call's.  A caller checks
+ * accept_len[b] < 0 (lpp_commit_kv commits nothing but the root for such an item) or asks:
+ *   lpp_tree_walk_status   [host] gave_up = number of walks that gave up since the handle was made or
+ *                          last reset.  Copies one word back from the device: it waits for the device
+ *                          (not for use inside a capture).
+ *   lpp_tree_walk_reset    enqueues on `stream` the kernel that sets that count (and the handle's other
+ *                          walk words) back to zero; never needed for correctness.
  *   lpp_tree_set_walk_patience   rounds (about 0.5 us each) the walking block waits: default and maximum
  *                          2^19; -1 makes the walk give up at once (for tests of the caller's handling).
  * Errors: LPP_EINVAL (null, rounds < -1), LPP_EHIP (host-only handle, copy or launch failed).
@@ -206,8 +209,8 @@ int32_t lpp_tree_attention_layers(const lpp_tree* tree, int32_t dtype, int32_t o
  * a stream.  When B * M blocks fit the device at once, the walk of an item is done by one of
  * its row blocks, which waits for the others' results; that wait is bounded, and nobody waits
  * for that block.  Should it ever run out (it cannot unless the other blocks of the launch do
- * not run), accept_len[b], path[b, :] and final_token[b] are set to -1, and so are those of
- * every later call with this handle until lpp_tree_walk_reset; lpp_tree_walk_status tells.
+ * not run), accept_len[b], path[b, :] and final_token[b] of that call are set to -1 (later calls
+ * are not affected); lpp_tree_walk_status counts such walks.
  */
 typedef struct lpp_verify_out {
   int32_t* accept_len;     /* [device] [B]        number of accepted drafted nodes            */

@@ -118,10 +118,11 @@ class Tree:
         _check(lib().lpp_tree_info(self.handle, *[C.byref(x) for x in v]), "lpp_tree_info")
         self.M, self.depth, self.n_parents, self.max_children = [x.value for x in v]
 
-    def walk_gave_up(self) -> bool:
+    def walk_gave_up(self) -> int:
+        """Number of walks that gave up since the handle was made or last reset."""
         v = C.c_int32()
         _check(lib().lpp_tree_walk_status(self.handle, C.byref(v)), "lpp_tree_walk_status")
-        return bool(v.value)
+        return int(v.value)
 
     def walk_reset(self, stream=None) -> None:
         _check(lib().lpp_tree_walk_reset(self.handle, _stream(stream)), "lpp_tree_walk_reset")

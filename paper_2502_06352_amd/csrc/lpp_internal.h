@@ -32,10 +32,12 @@ struct lpp_tree {
   // share one handle must therefore be ordered on a stream.
   int32_t* d_counters = nullptr;   // [2 * LPP_COUNTER_SLOTS]: verify, then attention
   // verify with the whole grid resident: words the rows leave for the block that walks
-  // ([LPP_MAX_ROWS] decisions, [LPP_MAX_ROWS] draws: -1 between calls; then one word that is
-  // raised for good when a walk gave up)
-  int32_t* d_mail = nullptr;       // [2 * LPP_MAX_ROWS + 1]
+  // ([LPP_MAX_ROWS] decisions, [LPP_MAX_ROWS] draws, each tagged with its call; then the number
+  // of walks that gave up)
+  int32_t* d_mail = nullptr;       // [kMailWords], zero when the handle is made
 };
+constexpr int kMailGaveUp = 2 * LPP_MAX_ROWS;
+constexpr int kMailWords = 2 * LPP_MAX_ROWS + 1;
 
 #define LPP_COUNTER_SLOTS 4096
 

@@ -89,10 +89,9 @@ extern "C" int32_t lpp_tree_create(const int32_t* parent_host, int32_t M, lpp_tr
   const size_t b_cnt = sizeof(int32_t) * 2 * LPP_COUNTER_SLOTS;
   if (hipMalloc((void**)&t->d_counters, b_cnt) != hipSuccess) return fail();
   if (hipMemset(t->d_counters, 0, b_cnt) != hipSuccess) return fail();
-  const size_t b_mail = sizeof(int32_t) * 2 * LPP_MAX_ROWS;
-  if (hipMalloc((void**)&t->d_mail, b_mail + sizeof(int32_t)) != hipSuccess) return fail();
-  if (hipMemset(t->d_mail, 0xFF, b_mail) != hipSuccess) return fail();
-  if (hipMemset(t->d_mail + 2 * LPP_MAX_ROWS, 0, sizeof(int32_t)) != hipSuccess) return fail();
+  const size_t b_mail = sizeof(int32_t) * kMailWords;
+  if (hipMalloc((void**)&t->d_mail, b_mail) != hipSuccess) return fail();
+  if (hipMemset(t->d_mail, 0, b_mail) != hipSuccess) return fail();
   if (hipMemcpy(t->d_child_ptr, t->child_ptr.data(), b_ptr, hipMemcpyHostToDevice) != hipSuccess) return fail();
   if (hipMemcpy(t->d_child_idx, t->child_idx.data(), b_idx, hipMemcpyHostToDevice) != hipSuccess) return fail();
   if (hipMemcpy(t->d_anc, t->anc.data(), b_anc, hipMemcpyHostToDevice) != hipSuccess) return fail();
@@ -124,8 +123,7 @@ extern "C" int32_t lpp_tree_info(const lpp_tree* t, int32_t* M, int32_t* depth, 
 // ---- state of the walk done by a resident block (lpp_relaxed_verify when B * M blocks fit the device)
 namespace {
 __global__ void mail_reset_kernel(int32_t* mail) {
-  for (int i = threadIdx.x; i < 2 * LPP_MAX_ROWS; i += blockDim.x) mail[i] = -1;
-  if (threadIdx.x == 0) mail[2 * LPP_MAX_ROWS] = 0;
+  for (int i = threadIdx.x; i < kMailWords; i += blockDim.x) mail[i] = 0;
 }
 }  // namespace
 
@@ -140,8 +138,8 @@ extern "C" int32_t lpp_tree_walk_status(const lpp_tree* t, int32_t* gave_up) {
   *gave_up = 0;
   if (!t->d_mail) return LPP_EHIP;
   int32_t flag = 0;
-  LPP_HIP_TRY(hipMemcpy(&flag, t->d_mail + 2 * LPP_MAX_ROWS, sizeof(int32_t), hipMemcpyDeviceToHost));
-  *gave_up = flag != 0;
+  LPP_HIP_TRY(hipMemcpy(&flag, t->d_mail + kMailGaveUp, sizeof(int32_t), hipMemcpyDeviceToHost));
+  *gave_up = flag;
   return LPP_OK;
 }
 

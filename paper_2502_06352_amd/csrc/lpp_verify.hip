@@ -251,19 +251,31 @@ __device__ __forceinline__ void walk_wave(const int32_t* word, const int32_t* fi
 
 // Walk of one item when the whole grid is resident at once (one wave of the block that walks).
 // Every other row of the item leaves its words -- (parent << 1 | decision) per child, its draw --
-// in `mail` (device-scope stores; -1 = not there yet), this wave asks for them until none is
-// missing, puts -1 back for the next call and walks as above.  Nobody waits for this block, so
-// the wait ends as soon as the other blocks have run; it is bounded all the same (`spin_limit`
-// rounds of loads): when the bound is hit the item's accept_len, path and final token are set
-// to -1 and mail[2 * LPP_MAX_ROWS] is raised, which makes every later call on this tree fail
-// the same way (words may arrive after this call gave up: the mail is no longer clean).
+// in `mail` (device-scope stores), this wave asks for them until none is missing and walks as
+// above.  Nobody waits for this block, so the wait ends as soon as the other blocks have run; it
+// is bounded all the same (`spin_limit` rounds of loads): when the bound is hit the item's
+// accept_len, path and final token are set to -1 and the count in mail[kMailGaveUp] goes up.
+//
+// Words carry a tag in their upper bits (kMailTagShift) that changes from call to call, so a
+// word that arrives after its call's walk gave up is not taken for the next call's, and nothing
+// has to be cleared between calls.  Every row block, the walking one too, owns one word of the
+// mail (its draw's); it reads the tag that word holds when it starts -- the one its own last call
+// left there, calls on one handle being ordered on a stream -- and uses the next one (1..1023
+// round and round; memory that was zeroed holds tag 0, which no call uses) for everything it
+// sends.  All rows of an item therefore step through the same tags, call after call.
 // s_own: [M] words of this block's own children, -1 elsewhere; s_next, s_fin: M ints each;
 // *s_end: row the path ended on (-1: failed), for the wave that holds this block's own draw.
 // The first round of loads is issued by the caller ahead of time (mail_fetch), so that it is in
 // flight while this wave still has other work.
+constexpr int kMailTagShift = 20;                    // payloads are below 2^20 (row << 1 | decision; a token)
+constexpr uint32_t kMailPayload = (1u << kMailTagShift) - 1u;
+// The tag that follows the one in `last_word`, in place.
+__device__ __forceinline__ uint32_t next_tag(uint32_t last_word) {
+  const uint32_t last_tag = last_word >> kMailTagShift;
+  return (last_tag >= 1023u ? 1u : last_tag + 1u) << kMailTagShift;
+}
 struct MailRound {
   int w[LPP_MAX_ROWS / 64], f[LPP_MAX_ROWS / 64];
-  int gave_up;
 };
 __device__ __forceinline__ void mail_fetch(MailRound& r, const int32_t* mail, int64_t nodebase, int M, int lane) {
 #pragma unroll
@@ -272,15 +284,12 @@ __device__ __forceinline__ void mail_fetch(MailRound& r, const int32_t* mail, in
     r.w[q] = __hip_atomic_load(&mail[nodebase + ic], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     r.f[q] = __hip_atomic_load(&mail[LPP_MAX_ROWS + nodebase + ic], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  r.gave_up = __hip_atomic_load(&mail[2 * LPP_MAX_ROWS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void collect_and_walk(MailRound r, int32_t* mail, int64_t nodebase, int M, int depth,
-                                                 int P, int spin_limit, int lane, const int* s_own, int* s_next,
-                                                 int* s_fin, int* s_end, int32_t* accept_len, int32_t* path,
-                                                 int32_t* final_token) {
+__device__ __forceinline__ void collect_and_walk(MailRound r, int32_t* mail, uint32_t tagw, int64_t nodebase, int M,
+                                                 int depth, int P, int spin_limit, int lane, const int* s_own,
+                                                 int* s_next, int* s_fin, int* s_end, int32_t* accept_len,
+                                                 int32_t* path, int32_t* final_token) {
   constexpr int Q = LPP_MAX_ROWS / 64;
-  int32_t* md = mail + nodebase;
-  int32_t* mf = mail + LPP_MAX_ROWS + nodebase;
   int wd[Q], fn[Q];
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
@@ -290,13 +299,13 @@ __device__ __forceinline__ void collect_and_walk(MailRound r, int32_t* mail, int
   }
   bool ok = false;
   // (a negative limit makes the walk give up at once: the host's way to exercise that path)
-  if (r.gave_up == 0 && spin_limit >= 0) {
+  if (spin_limit >= 0) {
     for (int spin = 0;; ++spin) {
       bool missing = false;
 #pragma unroll
       for (int q = 0; q < Q; ++q) {
-        if (wd[q] == -1) wd[q] = r.w[q];
-        if (fn[q] == -1) fn[q] = r.f[q];
+        if (wd[q] == -1 && ((uint32_t)r.w[q] & ~kMailPayload) == tagw) wd[q] = (int)((uint32_t)r.w[q] & kMailPayload);
+        if (fn[q] == -1 && ((uint32_t)r.f[q] & ~kMailPayload) == tagw) fn[q] = (int)((uint32_t)r.f[q] & kMailPayload);
         missing = missing || wd[q] == -1 || fn[q] == -1;
       }
       if (!__ballot(missing)) { ok = true; break; }
@@ -307,7 +316,7 @@ __device__ __forceinline__ void collect_and_walk(MailRound r, int32_t* mail, int
   }
   if (!ok) {
     if (lane == 0) {
-      __hip_atomic_store(&mail[2 * LPP_MAX_ROWS], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(&mail[kMailGaveUp], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       for (int i = 0; i < depth; ++i) path[i] = -1;
       *accept_len = -1;
       *final_token = -1;
@@ -319,8 +328,6 @@ __device__ __forceinline__ void collect_and_walk(MailRound r, int32_t* mail, int
   for (int q = 0; q < Q; ++q) {
     const int i = lane + 64 * q;
     if (i < M) {
-      __hip_atomic_store(&md[i], -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // ready for the next call
-      __hip_atomic_store(&mf[i], -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_fin[i] = fn[q];
       s_next[i] = INT_MAX;
     }
@@ -749,6 +756,7 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
   // 64 and up, before they leave): the per-child chain below then carries no global stores.
   float k_m = 0.f, k_qt = 0.f, k_pt = 0.f;
   int k_j = 0;
+  uint32_t tagw = 0;         // (whole grid resident) this call's tag, in place for the mail words
   auto write_children = [&](int first, int count) {
     if (lane < count) {
       const int cc = first + lane;
@@ -758,7 +766,8 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
       // what the walk needs of this node: a device-scope store, visible to every compute unit
       // once it has completed (no cache write-back needed before the ticket, or for the block that walks)
       if (!(STAG && walker))
-        __hip_atomic_store(&a.ws_decision[nodebase + c], (P << 1) | dec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&a.ws_decision[nodebase + c], (int)(tagw | (uint32_t)((P << 1) | dec)), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
       if (a.decision) a.decision[nodebase + c] = (uint8_t)dec;
       if (a.ratio) a.ratio[nodebase + c] = k_m / pt;
       if (a.mass) a.mass[nodebase + c] = k_m;
@@ -987,6 +996,16 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
     }
   }
 
+  // (whole grid resident) the word this row left in the mail last time holds the last call's tag;
+  // this call's is the next one.  Asked for now, looked at after the cell sums: a load still on its
+  // way while the children are taken is waited for in there.  (A vector load at one address for
+  // all lanes: as a wave-uniform value it would be waited for on the spot.)
+  uint32_t last_word = 0;
+  if (STAG) {
+    int lane_zero = 0;
+    asm("" : "+v"(lane_zero));
+    last_word = (uint32_t)a.ws_final[nodebase + P + lane_zero];
+  }
   MailRound mail_first;      // (the wave that walks) asked for now, looked at after the cell sums
   if (STAG && walker && w == 1) mail_fetch(mail_first, a.ws_decision, nodebase, a.M, lane);
   // ---- draw from the final r by inverse CDF over ascending token index: cell sums by
@@ -1017,6 +1036,7 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
   if (w != 0 && nchild > 64 * w) {
     // (rare: more than 64 children)  this wave's stores have to be complete before wave 0 takes
     // the row's ticket, which it does after the barrier below
+    tagw = STAG ? next_tag(last_word) : 0u;
     write_children(64 * w, min(nchild - 64 * w, 64));
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
     __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
@@ -1030,10 +1050,13 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
   lds_barrier();
   if (w != 0) {
     if (!(STAG && walker)) return;
+    tagw = STAG ? next_tag(last_word) : 0u;
     if (w == 1)
-      collect_and_walk(mail_first, a.ws_decision, nodebase, a.M, a.depth, P, a.spin_limit, lane, s_mail, s_mail + LPP_MAX_ROWS,
-                       s_mail + 2 * LPP_MAX_ROWS, s_mail + 3 * LPP_MAX_ROWS, a.accept_len + b,
+      collect_and_walk(mail_first, a.ws_decision, tagw, nodebase, a.M, a.depth, P, a.spin_limit, lane, s_mail,
+                       s_mail + LPP_MAX_ROWS, s_mail + 2 * LPP_MAX_ROWS, s_mail + 3 * LPP_MAX_ROWS, a.accept_len + b,
                        a.path + (int64_t)b * a.depth, a.final_token + b);
+    // (the walking block's own word is read by nobody but itself, next call: it keeps the tags in step)
+    if (w == 1 && lane == 0) a.ws_final[nodebase + P] = (int)tagw;
     lds_barrier();           // (met by wave 0 once it holds the draw)
     return;
   }
@@ -1097,6 +1120,7 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
     x = __builtin_amdgcn_readlane(tb + 4 * lane + e, l);
   }
   x = min(x, V - 1);
+  tagw = STAG ? next_tag(last_word) : 0u;
   write_children(0, min(nchild, 64));
   int ticket = 0;
   if (lane == 0) {
@@ -1110,7 +1134,7 @@ __global__ __launch_bounds__(NT, (STAG || ALT || FRONT || NT > 512) ? 1 : 4) voi
       if (a.p_tok) a.p_tok[nodebase] = 0.f;
     }
     if (!(STAG && walker))
-      __hip_atomic_store(&a.ws_final[nodebase + P], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&a.ws_final[nodebase + P], (int)(tagw | (uint32_t)x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (a.final_all) a.final_all[nodebase + P] = x;
     if (!STAG && a.counters) {
       // every store of this row's decisions and draw was issued by this wave: once they have

@@ -68,6 +68,23 @@ def test_verify_row_with_more_children_than_a_wave_has_lanes(B):
     compare_verify(parent, x, neigh, cfg.V, 0, cfg.k, cfg.lam, got, rule="skip", siblings="without_replacement")
 
 
+def test_verify_two_rows_with_more_children_than_a_wave_has_lanes():
+    # 70 children of the root and 70 of its first child (141 blocks, the whole grid resident): the
+    # root's block walks; row 1 does not, and its second wave sends children 64..69 on their way to
+    # the walking block itself.  Twice on one handle, with other inputs.
+    cfg = CONFIGS[1].scaled(V=1024, ldv=1024, k=16, B=1)
+    parent = np.array([-1] + [0] * 70 + [1] * 70, dtype=np.int32)
+    tree = lpp.Tree(parent)
+    E = make_codebook(cfg)
+    for salt in (0, 1):
+        x = make_verify_inputs(cfg, parent, rho=0.3, salt=salt)
+        neigh = sparse_neighbour_table(E, cfg.k, x["tokens"][:, 1:], cfg.V)
+        got = run_verify(tree, x, neigh, cfg.V, 0, cfg.ldv, cfg.k, cfg.lam)
+        rep = compare_verify(parent, x, neigh, cfg.V, 0, cfg.k, cfg.lam, got)
+        assert rep["nodes"] + rep["skipped_after_tie"] == 140
+    assert tree.walk_gave_up() == 0
+
+
 def test_verify_more_items_than_walk_counters():
     cfg = CONFIGS[1].scaled(V=64, ldv=64, k=4, N=3, branching=(2, 1), B=4100)
     # (tiny vocabulary, drafter close to the target: siblings often repeat a token, the input on which

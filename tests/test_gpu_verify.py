@@ -147,31 +147,58 @@ def test_verify_walk_by_a_row_other_than_the_root_and_repeated_calls():
         assert rep["nodes"] > 0
 
 
-def test_verify_walk_that_gives_up_is_loud_and_can_be_reset():
+def test_verify_walk_that_gives_up_is_loud_and_harms_no_later_call():
     # The bounded wait of the walking block is made to run out from the host (no kernel hangs or
-    # faults: the block just does not look at the results).  The call must say so in its outputs,
-    # the handle must stay marked and say so when asked, and a reset must make it good again.
+    # faults: the block just does not look at the results).  The call must say so in its outputs
+    # and the handle must count it; the rows' results of that call, which nobody took, must not be
+    # taken for the next call's: the next calls, with other inputs, match the oracle with no reset.
     cfg = CONFIGS[1]
     parent = static_tree(cfg.branching, cfg.N)
-    x = make_verify_inputs(cfg, parent, rho=0.8)
-    neigh = sparse_neighbour_table(make_codebook(cfg), cfg.k, x["tokens"][:, 1:], cfg.V)
+    E = make_codebook(cfg)
     tree = lpp.Tree(parent)
-    assert not tree.walk_gave_up()
-    tree.set_walk_patience(-1)
-    got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam, want_all=False)
-    assert np.all(got["accept_len"] == -1) and np.all(got["final_token"] == -1) and np.all(got["path"] == -1)
-    assert tree.walk_gave_up()
-    tree.set_walk_patience(1 << 19)
-    got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam, want_all=False)
-    assert np.all(got["accept_len"] == -1) and np.all(got["final_token"] == -1)
-    tree.walk_reset()
-    torch.cuda.synchronize()
-    assert not tree.walk_gave_up()
-    for _ in range(2):
+    assert tree.walk_gave_up() == 0
+
+    def good_call(salt):
+        x = make_verify_inputs(cfg, parent, rho=0.8, salt=salt)
+        neigh = sparse_neighbour_table(E, cfg.k, x["tokens"][:, 1:], cfg.V)
         got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam)
         compare_verify(parent, x, neigh, cfg.V, cfg.vocab_offset, cfg.k, cfg.lam, got)
+
+    good_call(0)
+    for round_ in range(2):
+        x = make_verify_inputs(cfg, parent, rho=0.8, salt=10 + round_)
+        neigh = sparse_neighbour_table(E, cfg.k, x["tokens"][:, 1:], cfg.V)
+        tree.set_walk_patience(-1)
+        got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam, want_all=False)
+        assert np.all(got["accept_len"] == -1) and np.all(got["final_token"] == -1) and np.all(got["path"] == -1)
+        assert tree.walk_gave_up() == (round_ + 1) * cfg.B
+        tree.set_walk_patience(1 << 19)
+        good_call(20 + round_)      # other inputs: a stale word taken for this call's would show
+        good_call(30 + round_)
+    tree.walk_reset()
+    torch.cuda.synchronize()
+    assert tree.walk_gave_up() == 0
+    good_call(40)
     with pytest.raises(lpp.LppError):
         tree.set_walk_patience(-2)
+
+
+def test_verify_many_calls_on_one_handle_tags_wrap():
+    # The call number inside the rows' words wraps after 512 calls: 600 calls on one handle, the
+    # last ones checked (inputs alternate, so a word of the call before would be a wrong one).
+    cfg = CONFIGS[1]
+    parent = static_tree(cfg.branching, cfg.N)
+    E = make_codebook(cfg)
+    tree = lpp.Tree(parent)
+    xs = [make_verify_inputs(cfg, parent, rho=0.8, salt=s) for s in (0, 1)]
+    neigh = sparse_neighbour_table(E, cfg.k, np.concatenate([x["tokens"][:, 1:].ravel() for x in xs]), cfg.V)
+    for i in range(600):
+        x = xs[i % 2]
+        got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam, want_all=False)
+        if i in (0, 1, 510, 511, 512, 513, 598, 599):
+            got = run_verify(tree, x, neigh, cfg.V, cfg.vocab_offset, cfg.ldv, cfg.k, cfg.lam)
+            compare_verify(parent, x, neigh, cfg.V, cfg.vocab_offset, cfg.k, cfg.lam, got)
+    assert tree.walk_gave_up() == 0
 
 
 @pytest.mark.parametrize("B,parent", [(120, [-1, 0]), (85, [-1, 0, 0]), (64, [-1, 0, 1, 2])])
