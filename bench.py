@@ -56,6 +56,9 @@ def main():
                     help="leave out the cache-resident pass (so that a kernel trace of this run holds HBM-resident "
                          "calls only)")
     ap.add_argument("--no-knn-timing", action="store_true", help="build the neighbour table once, untimed")
+    ap.add_argument("--no-two-batches", action="store_true",
+                    help="leave out the pass with two batches in flight (so that a kernel trace of this run holds "
+                         "kernels that had the device to themselves only)")
     ap.add_argument("--frontend", action="store_true",
                     help="verify through lpp_relaxed_verify_sampled (guidance 3.0 + top-k 2000 fused; reads one more "
                          "target row set); not the headline configuration")
@@ -193,8 +196,11 @@ def main():
     dtype = lpp.LPP_BF16 if cfg.kv_dtype == "bf16" else lpp.LPP_F32
     stream = torch.cuda.current_stream()
 
-    def attention(d, st=None):
+    ctx0 = {"tree": tree, "attn_ws": attn_ws, "ver_ws": ver_ws}
+
+    def attention(d, st=None, ctx=ctx0):
         st = stream if st is None else st
+        tree, attn_ws = ctx["tree"], ctx["attn_ws"]
         if L > 1 and not args.layer_loop:
             lpp.lpp_tree_attention_layers(tree, dtype, lpp.LPP_BF16 if args.out_bf16 else lpp.LPP_F32, d["layer_table"],
                                           None, B, H, Hkv, S, Dh, 0.0, attn_ws, st)
@@ -208,8 +214,9 @@ def main():
                 lpp.lpp_tree_attention(tree, dtype, x["q"], x["kc"], x["vc"], x["kt"], x["vt"], None,
                                        B, H, S, Dh, 0.0, d["out_attn"], attn_ws, st)
 
-    def verify(d, st=None):
+    def verify(d, st=None, ctx=ctx0):
         st = stream if st is None else st
+        tree, ver_ws = ctx["tree"], ctx["ver_ws"]
         if args.rule != "prefix" or args.siblings != "iid":
             lpp.lpp_relaxed_verify_opts(tree, d["target_logits"], d["drafter_logits"], cfg.ldv, cfg.vocab_offset, V, B,
                                         d["tokens"], neigh, k, k, d["u_accept"], d["u_final"], d["vout"], ver_ws, st,
@@ -330,6 +337,42 @@ def main():
     ver_d = dist(replay_samples(g_ver, lambda: [verify(d) for d in reps], n_rep_d, R))
     attn_ms, verify_ms = attn_d["mean"], ver_d["mean"]
 
+    # ---- two batches in flight (a server with two independent sequences' batches): the replicas
+    # are dealt to two branches of one graph, each branch a chain of whole steps with a tree handle
+    # and workspaces of its own, so the attention of one batch runs beside the verify of the other.
+    # Reported beside `value`, never in place of it: `value` is one batch, its steps one after the other.
+    two = None
+    if launch == "hipgraph" and L == 1 and R >= 2 and not args.no_two_batches:
+        try:
+            ctx1 = {"tree": lpp.Tree(parent), "attn_ws": torch.empty_like(attn_ws), "ver_ws": torch.empty_like(ver_ws)}
+            s2 = torch.cuda.Stream()
+
+            def two_branches():
+                s2.wait_stream(side)
+                for d in reps[0::2]:
+                    attention(d, side, ctx0)
+                    verify(d, side, ctx0)
+                for d in reps[1::2]:
+                    attention(d, s2, ctx1)
+                    verify(d, s2, ctx1)
+                side.wait_stream(s2)
+
+            for d in reps[1::2]:               # eager warm-up of the second handle
+                attention(d, stream, ctx1)
+                verify(d, stream, ctx1)
+            torch.cuda.synchronize()
+            g_two = capture(two_branches)
+            torch.cuda.synchronize()
+            two_d = dist(replay_samples(g_two, None, n_rep_d, R))
+            gave_up = tree.walk_gave_up() + ctx1["tree"].walk_gave_up()
+            two = {"value": 1e3 / two_d["mean"], "unit": "steps/s", "ms_per_step": round(two_d["mean"], 5),
+                   "ms_per_step_median": round(two_d["median"], 5), "batches_in_flight": 2,
+                   "walks_that_gave_up": gave_up,
+                   "note": "two independent batches, one graph branch each (own tree handle and workspaces); "
+                           "every step still runs attention then verify in order"}
+        except Exception as e:         # pragma: no cover - depends on the runtime
+            two = {"value": None, "note": "not measured (%s)" % type(e).__name__}
+
     # ---- streaming-read ceiling of this device: a plain read of 1 GiB (four times the last-level
     # cache) by the library's probe kernel, best of a few grid sizes
     stream_gbs = None
@@ -428,7 +471,7 @@ def main():
                       "attention_layers_per_step": L, "kv_heads": Hkv,
                       "attention_out": "bf16" if args.out_bf16 else "f32",
                       "launch": launch},
-           "roofline": roofline, "cpu_baseline": cpu, "knn_build": knn}
+           "roofline": roofline, "cpu_baseline": cpu, "knn_build": knn, "two_batches_in_flight": two}
     print(json.dumps(out))
 
 
