@@ -415,7 +415,8 @@ def main():
     knn = None
     if knn_ms:
         knn_flops = 2.0 * V * V * cfg.D             # the method's contraction: every pair of codes once
-        knn = {"ms": knn_ms, "mfma_dtype": "f32", "contraction_TFLOPs": knn_flops / (knn_ms * 1e-3) / 1e12,
+        knn = {"ms": knn_ms, "mfma_dtype": "f32" if cfg.D <= 16 else "bf16 filter, float64 keys",
+               "contraction_TFLOPs": knn_flops / (knn_ms * 1e-3) / 1e12,
                "frac_of_fp32_mfma_peak": knn_flops / (knn_ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS,
                "note": "one-time per codebook; whole build (select, float64 re-rank, ordering) against the 2 V^2 D "
                        "flops of the definition; sweeps beyond the first are not counted as work"}

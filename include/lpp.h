@@ -101,8 +101,9 @@ int32_t lpp_tree_set_walk_patience(lpp_tree* tree, int32_t rounds);
  * One-time per codebook.  Errors: LPP_EINVAL (null, V < 1, D < 1, k < 1, k > V),
  * LPP_EUNSUPPORTED (k > LPP_MAX_K, D > 256, V > 65536), LPP_ENOWORKSPACE, LPP_EHIP.
  * A codebook so degenerate that more than k + 1024 codes tie with the k-th
- * neighbour of some code (within float32 rounding) is still handled exactly by a
- * slower per-row path.
+ * neighbour of some code (within the rounding of the filter: float32 for rows of up
+ * to 16 floats, bfloat16 operands for longer ones) is still handled exactly by a
+ * slower per-row path; so are rows far from unit length.
  */
 size_t  lpp_build_neighbours_workspace(int32_t V, int32_t D, int32_t k);
 int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, int32_t k,

@@ -6,16 +6,21 @@
 // cores round.  Three kernels:
 //   pack    zero-padded copy of the codebook (rows of DP floats, DP = 16..256 a power of two >= D), row
 //           norms and their maximum (for the rounding bound below).
-//   select  the dense V x V contraction on the fp32 matrix cores (MFMA 16x16x4),
-//           swept twice per block of 64 codes and never written out: sweep 1
-//           histograms each row's similarities into 1024 bins and finds the bin
-//           b* holding the (k-1)-th largest; sweep 2 appends every code whose bin
-//           is >= b* - 1 to the row's candidate list.
+//   select  the dense V x V contraction on the matrix cores, swept twice per block of
+//           query codes and never written out: sweep 1 histograms each row's
+//           similarities into 1024 bins and finds the bin b* holding the (k-1)-th
+//           largest; sweep 2 appends every code whose bin is >= b* - 1 - m to the
+//           row's candidate list.  Rows of up to 16 floats: fp32 MFMA 16x16x4, 16
+//           queries per block, m = 0.  Longer rows: the sweeps are bound by streaming
+//           the codebook out of the last-level cache once per block and sweep, so they
+//           run on a bf16 copy of it (half the bytes, MFMA 16x16x32) with 32 queries
+//           per block (half the blocks), and m bins of margin make up for the rounding
+//           of the copy (see row_eps).
 //   rank    per row: exact float64 keys of the candidates (FMA chain in index
 //           order), rank by (key desc, index asc) with value buckets in LDS, write the row.
 // Why the candidate list is enough: a code that is not a candidate has an
-// approximate similarity below the lower edge e of bin b* - 1, hence an exact key
-// below e + eps, eps bounding the matrix-core rounding.  If the (k-1)-th exact key
+// approximate similarity below the lower edge e of the lowest bin taken, hence an exact
+// key below e + eps, eps bounding the rounding of the approximate similarity.  If the (k-1)-th exact key
 // among the candidates is >= e + eps, no outsider can belong to the row.  Rows
 // that fail this test, or overflow the candidate list, take an exact (slow)
 // radix-select path over all V codes instead.
@@ -32,11 +37,14 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef double f64x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kBins = 1024;
 constexpr float kBinScale = 512.0f;           // bin = floor((s + 1) * 512), clamped
 constexpr int kSelWaves = 4;
 constexpr int kSelRows = 16;                  // query codes per select block
+constexpr int kSel2Waves = 8;                 // the bf16 sweeps: 8 waves and
+constexpr int kSel2Rows = 32;                 // 32 query codes per block
 constexpr int kRankThreads = 256;
 constexpr int kSlack = 1024;                  // candidate list = k - 1 + slack (rounded)
 
@@ -44,9 +52,10 @@ struct KnnArgs {
   const float* E;
   int32_t V, D, DP, Vp, k, cap;
   float* Ep;            // [Vp][DP]
+  uint16_t* Eh;         // [Vp][DP] bf16 (round to nearest even) of Ep, or null: the sweeps run in fp32
   float* norms;         // [Vp]
   uint32_t* maxnorm;    // float bits
-  int32_t* bstar;       // [Vp]
+  int32_t* bstar;       // [Vp] lowest bin whose codes became candidates
   int32_t* cnt;         // [Vp]
   uint16_t* cand;       // [V][cap]
   int32_t* neigh;       // [V][k]
@@ -70,6 +79,12 @@ __global__ __launch_bounds__(256) void knn_pack_kernel(KnnArgs a) {
       float v = 0.f;
       if (row < a.V && d < a.D) v = a.E[(int64_t)row * a.D + d];
       a.Ep[(int64_t)row * a.DP + d] = v;
+      if (a.Eh) {
+        const uint32_t u = __float_as_uint(v);
+        // round to nearest even on the upper 16 bits; NaN stays NaN (quiet bit set)
+        const uint32_t h = (u & 0x7FFFFFFFu) > 0x7F800000u ? ((u >> 16) | 0x40u) : ((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+        a.Eh[(int64_t)row * a.DP + d] = (uint16_t)h;
+      }
       ss += v * v;
     }
 #pragma unroll
@@ -82,6 +97,64 @@ __global__ __launch_bounds__(256) void knn_pack_kernel(KnnArgs a) {
   __syncthreads();
   if (threadIdx.x == 0)
     atomicMax(a.maxnorm, __float_as_uint(fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]))));
+}
+
+// Bound on |approximate - exact| similarity of row i with any code.  fp32 sweeps: the matrix
+// core's additions, (DP + 4) roundings of 2^-23 on sums of at most |e_i| |e_j|.  bf16 sweeps: each
+// operand carries a relative rounding of 2^-9, so each product one of 2^-8 + 2^-18 (the products
+// themselves are exact in fp32), summed: (2^-8 + 2^-18) sum |e_i,t e_j,t| <= that times |e_i| |e_j|;
+// plus the additions as before.  2.5e-7 covers the rounding of the bin map.
+__device__ __forceinline__ float row_eps(const KnnArgs& a, int i) {
+  const float add = (float)(a.DP + 4) * 1.1920929e-07f;
+  const float rel = a.Eh ? 0.00390625f * 1.01f + add : add;
+  return rel * a.norms[i] * __uint_as_float(*a.maxnorm) * 1.001f + 2.5e-7f;
+}
+// Bins of margin below b* - 1 that the candidates of row i take in.  The (k-1)-th largest
+// approximate similarity lies in bin b*, so the (k-1)-th exact key of the candidates is at least
+// b*'s lower edge less eps; the rank kernel's test wants it eps above the lower edge of the lowest
+// bin taken, b* - 1 - m: (1 + m) bins >= 2 eps.  (Huge for rows whose eps is: everything is taken.)
+__device__ __forceinline__ int row_margin(const KnnArgs& a, int i) {
+  if (!a.Eh) return 0;
+  const float m = ceilf(2.0f * row_eps(a, i) * kBinScale - 1.0f);
+  return m < (float)kBins ? (m > 0.f ? (int)m : 0) : kBins;      // (NaN norms: kBins)
+}
+
+// b* of one row's histogram (two 16-bit counts per word): the highest bin whose count from the top
+// reaches kk, 0 if none does.  One wave; every lane returns it.
+__device__ __forceinline__ int find_bstar(const uint32_t* h, int kk, int lane) {
+  // lane covers bins [1023 - 16*lane - 15, 1023 - 16*lane], scanned downwards
+  int cntv[16];
+  int local = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t w = h[(kBins / 2 - 1) - 8 * lane - j];   // bins (hi, lo) = (odd, even)
+    cntv[2 * j] = (int)(w >> 16);
+    cntv[2 * j + 1] = (int)(w & 0xFFFFu);
+    local += cntv[2 * j] + cntv[2 * j + 1];
+  }
+  int incl = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(incl, o);
+    if (lane >= o) incl += t;
+  }
+  const unsigned long long bal = __ballot(incl >= kk);
+  int bs = 0;
+  if (bal) {
+    const int fl = __ffsll((long long)bal) - 1;
+    int run = __shfl(incl - local, fl);
+    int found = 0;
+    if (lane == fl) {
+      found = kBins - 1 - 16 * lane - 15;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        run += cntv[j];
+        if (run >= kk) { found = kBins - 1 - 16 * lane - j; break; }
+      }
+    }
+    bs = __shfl(found, fl);
+  }
+  return bs;
 }
 
 // NS4 = float4 loads per lane and code (DP = 16 * NS4).  Contraction slot (step, g)
@@ -184,42 +257,10 @@ __global__ __launch_bounds__(kSelWaves * 64) void knn_select_kernel(KnnArgs a) {
     if (phase == 0) {
       // b* of each row: highest bin whose count-from-the-top reaches kk; a wave takes 4 of the 16 rows
       for (int r = wave * (kSelRows / kSelWaves); r < (wave + 1) * (kSelRows / kSelWaves); ++r) {
-        const uint32_t* h = s_hist + r * (kBins / 2);
-        // lane covers bins [1023 - 16*lane - 15, 1023 - 16*lane], scanned downwards
-        int cntv[16];
-        int local = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const uint32_t w = h[(kBins / 2 - 1) - 8 * lane - j];   // bins (hi, lo) = (odd, even)
-          cntv[2 * j] = (int)(w >> 16);
-          cntv[2 * j + 1] = (int)(w & 0xFFFFu);
-          local += cntv[2 * j] + cntv[2 * j + 1];
-        }
-        int incl = local;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const int t = __shfl_up(incl, o);
-          if (lane >= o) incl += t;
-        }
-        const unsigned long long bal = __ballot(incl >= kk);
-        int bs = 0;
-        if (bal) {
-          const int fl = __ffsll((long long)bal) - 1;
-          int run = __shfl(incl - local, fl);
-          int found = 0;
-          if (lane == fl) {
-            found = kBins - 1 - 16 * lane - 15;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-              run += cntv[j];
-              if (run >= kk) { found = kBins - 1 - 16 * lane - j; break; }
-            }
-          }
-          bs = __shfl(found, fl);
-        }
+        const int bs = find_bstar(s_hist + r * (kBins / 2), kk, lane);
         if (lane == 0) {
           s_bstar[r] = bs;
-          if (row0 + r < a.Vp) a.bstar[row0 + r] = bs;
+          if (row0 + r < a.Vp) a.bstar[row0 + r] = bs - 1;
         }
       }
       __syncthreads();
@@ -228,6 +269,122 @@ __global__ __launch_bounds__(kSelWaves * 64) void knn_select_kernel(KnnArgs a) {
     }
   }
   if (threadIdx.x < kSelRows && row0 + threadIdx.x < a.Vp) a.cnt[row0 + threadIdx.x] = s_cnt[threadIdx.x];
+}
+
+// The sweeps on the bf16 copy of the codebook.  KS = contraction steps of 32 (DP = 32 * KS).
+// A block owns 32 query codes -- two B operands per wave, so a code tile that was loaded feeds two
+// MFMA chains -- and its 8 waves take the code tiles (16 codes each) in turn; U tiles are in flight
+// per wave.  Slot (g, e) of a step is dimension 32*step + 8*g + e on both operands.
+template <int KS>
+__global__ __launch_bounds__(kSel2Waves * 64) void knn_select_bf16_kernel(KnnArgs a) {
+  constexpr int U = KS >= 8 ? 2 : 4;
+  extern __shared__ uint32_t s_hist[];          // [kSel2Rows][kBins/2], two 16-bit counts per word
+  __shared__ int s_cnt[kSel2Rows];
+  __shared__ int s_low[kSel2Rows];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l16 = lane & 15, g4 = lane >> 4;
+  const int row0 = blockIdx.x * kSel2Rows;              // the block's 32 query codes (Vp is a multiple of 64)
+  const int DP = a.DP, V = a.V;
+  const int kk = a.k - 1;
+  const int ntiles = a.Vp / 16;
+
+  bf16x8 qv[2][KS];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      qv[qt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
+          a.Eh + (int64_t)(row0 + 16 * qt + l16) * DP + 32 * ks + 8 * g4));
+
+  for (int i = threadIdx.x; i < kSel2Rows * (kBins / 2); i += kSel2Waves * 64) s_hist[i] = 0u;
+  if (threadIdx.x < kSel2Rows) s_cnt[threadIdx.x] = 0;
+  __syncthreads();
+
+  float thr[2] = {0.f, 0.f};
+  bool take_all[2] = {true, true};
+  const uint16_t* lane_row = a.Eh + (int64_t)l16 * DP + 8 * g4;
+  auto sweep = [&](auto phase_tag) {
+    constexpr int PHASE = decltype(phase_tag)::value;
+    for (int t0 = wave; t0 < ntiles; t0 += kSel2Waves * U) {
+      bf16x8 av[U][KS];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int t = min(t0 + kSel2Waves * u, ntiles - 1);     // (past the end: a re-read that is not used)
+        const uint16_t* arow = lane_row + (int64_t)t * (16 * DP);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          av[u][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(arow + 32 * ks));
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u][ks], qv[0][ks], acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u][ks], qv[1][ks], acc[1], 0, 0, 0);
+        }
+        const int t = t0 + kSel2Waves * u;
+        if (t >= ntiles) continue;
+        // tiles without the queries' own codes and without padding take no check per similarity
+        const bool plain = (t >> 1) != row0 / 32 && t * 16 + 16 <= V && row0 + kSel2Rows <= V;    // uniform
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+          // lane holds sim(code 16 t + 4*g4 + r, query row0 + 16 qt + l16), r = 0..3
+          const int qrow = row0 + 16 * qt + l16;
+          float x[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) x[r] = __builtin_fmaf(acc[qt][r], kBinScale, kBinScale);
+          if (PHASE == 0) {
+            uint32_t* my_hist = s_hist + (16 * qt + l16) * (kBins / 2);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int code = t * 16 + 4 * g4 + r;
+              const int bin = min(max((int)x[r], 0), kBins - 1);      // (int) truncates and sends NaN to 0
+              if (plain || !(code >= V || code == qrow || qrow >= V))
+                atomicAdd(&my_hist[bin >> 1], 1u << ((bin & 1) << 4));
+            }
+          } else {
+            bool pass[4];
+            bool any = false;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int code = t * 16 + 4 * g4 + r;
+              pass[r] = (take_all[qt] || x[r] >= thr[qt]) && (plain || !(code >= V || code == qrow || qrow >= V));
+              any = any || pass[r];
+            }
+            if (__ballot(any)) {
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+                if (pass[r]) {
+                  const int pos = atomicAdd(&s_cnt[16 * qt + l16], 1);
+                  if (pos < a.cap) a.cand[(int64_t)qrow * a.cap + pos] = (uint16_t)(t * 16 + 4 * g4 + r);
+                }
+            }
+          }
+        }
+      }
+    }
+  };
+  sweep(std::integral_constant<int, 0>());
+  __syncthreads();
+  // lowest bin taken, per row: b* - 1 less the margin for the rounding of the copy; a wave takes 4 rows
+  for (int r = wave * (kSel2Rows / kSel2Waves); r < (wave + 1) * (kSel2Rows / kSel2Waves); ++r) {
+    const int bs = find_bstar(s_hist + r * (kBins / 2), kk, lane);
+    if (lane == 0) {
+      const int low = row0 + r < a.Vp ? bs - 1 - row_margin(a, row0 + r) : 0;
+      s_low[r] = low;
+      if (row0 + r < a.Vp) a.bstar[row0 + r] = low;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    thr[qt] = (float)s_low[16 * qt + l16];
+    take_all[qt] = s_low[16 * qt + l16] <= 0;
+  }
+  sweep(std::integral_constant<int, 1>());
+  __syncthreads();
+  if (threadIdx.x < kSel2Rows && row0 + threadIdx.x < a.Vp) a.cnt[row0 + threadIdx.x] = s_cnt[threadIdx.x];
 }
 
 __device__ __forceinline__ uint64_t orderable(double x) {
@@ -431,11 +588,10 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
     __syncthreads();
     bucket_rank(skey, sidx, n, P, cur, ord, s_red, kk, out, &s_kth, tid);
     // can a code outside the candidate list still belong to the row?
-    const int bs = a.bstar[i];
-    if (bs - 1 >= 1) {
-      const float edge = (float)(bs - 1) / kBinScale - 1.0f;      // lower edge of bin b* - 1
-      const float eps = (float)(DP + 4) * 1.1920929e-07f * a.norms[i] * __uint_as_float(*a.maxnorm) * 1.001f + 2.5e-7f;   // (+ the rounding of the bin map itself)
-      slow = s_kth < orderable((double)edge + (double)eps);
+    const int low = a.bstar[i];
+    if (low >= 1) {
+      const float edge = (float)low / kBinScale - 1.0f;           // lower edge of the lowest bin taken
+      slow = s_kth < orderable((double)edge + (double)row_eps(a, i));
     }
     if (!slow) return;
     // the row was written from the candidate list and is written again below by other lanes:
@@ -508,7 +664,7 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
 int32_t cap_for(int32_t k) { return (int32_t)lpp_align_up((size_t)(k - 1) + kSlack, 64); }
 
 struct KnnLayout {
-  size_t o_ep, o_norms, o_max, o_bstar, o_cnt, o_cand, total;
+  size_t o_ep, o_eh, o_norms, o_max, o_bstar, o_cnt, o_cand, total;
   int32_t DP, Vp, cap;
 };
 
@@ -520,6 +676,7 @@ KnnLayout knn_layout(int32_t V, int32_t D, int32_t k) {
   L.cap = cap_for(k);
   size_t o = 0;
   L.o_ep = o;    o += lpp_align_up((size_t)L.Vp * L.DP * sizeof(float), 256);
+  L.o_eh = o;    o += L.DP >= 32 ? lpp_align_up((size_t)L.Vp * L.DP * sizeof(uint16_t), 256) : 0;
   L.o_norms = o; o += lpp_align_up((size_t)L.Vp * sizeof(float), 256);
   L.o_max = o;   o += 256;
   L.o_bstar = o; o += lpp_align_up((size_t)L.Vp * sizeof(int32_t), 256);
@@ -527,6 +684,18 @@ KnnLayout knn_layout(int32_t V, int32_t D, int32_t k) {
   L.o_cand = o;  o += lpp_align_up((size_t)V * L.cap * sizeof(uint16_t), 256);
   L.total = o;
   return L;
+}
+
+template <int KS>
+int32_t launch_select_bf16(const KnnArgs& a, hipStream_t s) {
+  const size_t lds = (size_t)kSel2Rows * (kBins / 2) * sizeof(uint32_t);
+  auto kern = knn_select_bf16_kernel<KS>;
+  static LppLdsLimit limit;
+  const int32_t st = lpp_ensure_lds(reinterpret_cast<const void*>(kern), limit, lds);
+  if (st != LPP_OK) return st;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.Vp / kSel2Rows)), dim3(kSel2Waves * 64), lds, s, a);
+  LPP_HIP_TRY(hipGetLastError());
+  return LPP_OK;
 }
 
 template <int NS4>
@@ -562,6 +731,7 @@ extern "C" int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, in
   KnnArgs a;
   a.E = E; a.V = V; a.D = D; a.DP = L.DP; a.Vp = L.Vp; a.k = k; a.cap = L.cap;
   a.Ep = reinterpret_cast<float*>(w + L.o_ep);
+  a.Eh = L.DP >= 32 ? reinterpret_cast<uint16_t*>(w + L.o_eh) : nullptr;
   a.norms = reinterpret_cast<float*>(w + L.o_norms);
   a.maxnorm = reinterpret_cast<uint32_t*>(w + L.o_max);
   a.bstar = reinterpret_cast<int32_t*>(w + L.o_bstar);
@@ -577,10 +747,10 @@ extern "C" int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, in
     int32_t st;
     switch (L.DP / 16) {
       case 1: st = launch_select<1>(a, s); break;
-      case 2: st = launch_select<2>(a, s); break;
-      case 4: st = launch_select<4>(a, s); break;
-      case 8: st = launch_select<8>(a, s); break;
-      case 16: st = launch_select<16>(a, s); break;
+      case 2: st = launch_select_bf16<1>(a, s); break;
+      case 4: st = launch_select_bf16<2>(a, s); break;
+      case 8: st = launch_select_bf16<4>(a, s); break;
+      case 16: st = launch_select_bf16<8>(a, s); break;
       default: st = LPP_EUNSUPPORTED; break;
     }
     if (st != LPP_OK) return st;

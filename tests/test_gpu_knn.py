@@ -87,6 +87,23 @@ def test_knn_unnormalised_rows_still_exact():
     E = (g.standard_normal((900, 8)) * g.uniform(0.2, 3.0, size=(900, 1))).astype(np.float32)
     got = run_knn(E, 100)
     _check_rows(E, 100, got, np.arange(900))
+    # rows of more than 16 floats go through the bfloat16 filter, whose margin grows with the norms
+    E = g.standard_normal((700, 40))
+    E = (E / np.linalg.norm(E, axis=1, keepdims=True) * g.uniform(0.5, 1.6, size=(700, 1))).astype(np.float32)
+    got = run_knn(E, 60)
+    _check_rows(E, 60, got, np.arange(700))
+
+
+def test_knn_long_rows_near_ties_below_bfloat16_resolution():
+    # Codes that differ from each other by far less than a bfloat16 rounding (1e-4 against 4e-3):
+    # the filter cannot tell them apart, the float64 keys must.  Clusters of 12 around 150 centres.
+    g = np.random.default_rng(7)
+    centres = g.standard_normal((150, 64))
+    E = np.repeat(centres, 12, axis=0) + 1e-4 * g.standard_normal((1800, 64))
+    E = (E / np.linalg.norm(E, axis=1, keepdims=True)).astype(np.float32)
+    for k in (8, 100):
+        got = run_knn(E, k)
+        _check_rows(E, k, got, np.arange(1800))
 
 
 def test_knn_deterministic_and_errors():
