@@ -46,7 +46,8 @@ constexpr int kSelRows = 16;                  // query codes per select block
 constexpr int kSel2Waves = 8;                 // the bf16 sweeps: 8 waves and
 constexpr int kSel2Rows = 32;                 // 32 query codes per block
 constexpr int kRankThreads = 256;
-constexpr int kSlack = 1024;                  // candidate list = k - 1 + slack (rounded)
+constexpr int kSlack = 1024;                  // candidate list = k - 1 + slack (rounded); rows of up to 16
+constexpr int kSlackShort = 512;              // floats spread their similarities widely: half of it
 
 struct KnnArgs {
   const float* E;
@@ -422,7 +423,7 @@ __device__ __forceinline__ double key_value(uint64_t K) {
 // bucket, and an entry's rank is its bucket's start plus the number of bucket mates that go
 // before it.  The first kk ranks are written to out[1 + rank]; the key of rank kk - 1 is left in
 // *kth.  cur[NB] and ord[n] are LDS scratch.  Ends with a barrier.
-__device__ void bucket_rank(const uint64_t* skey, const uint32_t* sidx, int n, int NB, uint32_t* cur,
+__device__ void bucket_rank(const uint64_t* skey, const uint16_t* sidx, int n, int NB, uint32_t* cur,
                             uint16_t* ord, uint64_t* s_red, int kk, int32_t* out, uint64_t* kth,
                             int tid) {
   const int lane = tid & 63, wv = tid >> 6;
@@ -523,7 +524,7 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
   if (tid == 0) out[0] = i;
   if (kk == 0) return;
   uint64_t* skey = reinterpret_cast<uint64_t*>(smem);
-  uint32_t* sidx = reinterpret_cast<uint32_t*>(skey + P);
+  uint16_t* sidx = reinterpret_cast<uint16_t*>(skey + P);     // (V <= 65536; P is a multiple of 256)
   double* eid = reinterpret_cast<double*>(sidx + P);     // the query row as doubles
   float* ei = reinterpret_cast<float*>(eid + DP);         // and as loaded (exact path)
   // scratch: staging tiles while keys are computed, then the buckets of the ranking
@@ -547,6 +548,32 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
       const int c = base + lane;
       const int jown = c < n ? (int)crow[c] : i;
       double acc = 0.0;
+      if (CH == 16) {
+        // rows of 16 floats are one 64-byte segment: every lane reads its own candidate's row, no tile
+        const float* er = a.Ep + (int64_t)jown * DP;
+        f32x4 v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const f32x4*>(er + 4 * q);
+        if (D == 16) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f64x2 e0 = *reinterpret_cast<const f64x2*>(eid + 4 * q);
+            const f64x2 e1 = *reinterpret_cast<const f64x2*>(eid + 4 * q + 2);
+            acc = __builtin_fma(e0[0], (double)v[q][0], acc);
+            acc = __builtin_fma(e0[1], (double)v[q][1], acc);
+            acc = __builtin_fma(e1[0], (double)v[q][2], acc);
+            acc = __builtin_fma(e1[1], (double)v[q][3], acc);
+          }
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (4 * q + e < D) acc = __builtin_fma(eid[4 * q + e], (double)v[q][e], acc);
+        }
+        if (c < n) { skey[c] = orderable(acc); sidx[c] = (uint16_t)jown; }
+        continue;
+      }
       f32x4 piece[LPR];
 #pragma unroll
       for (int q = 0; q < LPR; ++q) {
@@ -583,7 +610,7 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
         }
         wave_lds_sync();
       }
-      if (c < n) { skey[c] = orderable(acc); sidx[c] = (uint32_t)jown; }
+      if (c < n) { skey[c] = orderable(acc); sidx[c] = (uint16_t)jown; }
     }
     __syncthreads();
     bucket_rank(skey, sidx, n, P, cur, ord, s_red, kk, out, &s_kth, tid);
@@ -643,7 +670,7 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
       }
       if (gt) {
         const int pos = atomicAdd(&s_misc[2], 1);
-        skey[pos] = K; sidx[pos] = (uint32_t)j;
+        skey[pos] = K; sidx[pos] = (uint16_t)j;
       }
       // ordered compaction of the ties (ascending index)
       const unsigned long long bal = __ballot(eq);
@@ -652,7 +679,7 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
       int base = s_misc[3];
       for (int w = 0; w < wv; ++w) base += s_hist[w];
       const int rank = base + __popcll(bal & ((1ull << lane) - 1ull));
-      if (eq && rank < need) { skey[n_gt + rank] = K; sidx[n_gt + rank] = (uint32_t)j; }
+      if (eq && rank < need) { skey[n_gt + rank] = K; sidx[n_gt + rank] = (uint16_t)j; }
       __syncthreads();
       if (tid == 0) s_misc[3] += s_hist[0] + s_hist[1] + s_hist[2] + s_hist[3];
       __syncthreads();
@@ -661,7 +688,9 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
   }
 }
 
-int32_t cap_for(int32_t k) { return (int32_t)lpp_align_up((size_t)(k - 1) + kSlack, 64); }
+int32_t cap_for(int32_t k, int32_t DP) {
+  return (int32_t)lpp_align_up((size_t)(k - 1) + (DP <= 16 ? kSlackShort : kSlack), 64);
+}
 
 struct KnnLayout {
   size_t o_ep, o_eh, o_norms, o_max, o_bstar, o_cnt, o_cand, total;
@@ -673,7 +702,7 @@ KnnLayout knn_layout(int32_t V, int32_t D, int32_t k) {
   L.DP = 16;
   while (L.DP < D) L.DP <<= 1;             // 16, 32, ..., 256
   L.Vp = (int32_t)lpp_align_up((size_t)V, 64);
-  L.cap = cap_for(k);
+  L.cap = cap_for(k, L.DP);
   size_t o = 0;
   L.o_ep = o;    o += lpp_align_up((size_t)L.Vp * L.DP * sizeof(float), 256);
   L.o_eh = o;    o += L.DP >= 32 ? lpp_align_up((size_t)L.Vp * L.DP * sizeof(uint16_t), 256) : 0;
@@ -755,13 +784,13 @@ extern "C" int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, in
     }
     if (st != LPP_OK) return st;
   }
-  int P = kRankThreads;
-  while (P < L.cap) P <<= 1;
+  const int P = (int)lpp_align_up((size_t)L.cap, kRankThreads);
   const int CH = L.DP < 32 ? 16 : 32;
-  // keys + indices + the query row (as doubles and floats) + max(staging tiles, bucket counters and order)
-  const size_t stage = (size_t)(kRankThreads / 64) * 64 * (CH + 4) * sizeof(float);
+  // keys + indices + the query row (as doubles and floats) + max(staging tiles, bucket counters and order);
+  // rows of 16 floats need no staging tiles
+  const size_t stage = CH == 16 ? 0 : (size_t)(kRankThreads / 64) * 64 * (CH + 4) * sizeof(float);
   const size_t sortb = (size_t)P * 6;
-  const size_t lds = (size_t)P * 12 + (size_t)L.DP * 12 + (stage > sortb ? stage : sortb);
+  const size_t lds = (size_t)P * 10 + (size_t)L.DP * 12 + (stage > sortb ? stage : sortb);
   if (lds > 150 * 1024) return LPP_EUNSUPPORTED;
   static LppLdsLimit limit[2];   // (zero-initialised) one per kernel
   const void* fn = CH == 16 ? reinterpret_cast<const void*>(knn_rank_kernel<16>)
