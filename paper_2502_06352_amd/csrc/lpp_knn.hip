@@ -39,8 +39,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef double f64x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kBins = 1024;
+constexpr int kBins = 1024;                   // the bf16 sweeps: two 16-bit counts per LDS word,
 constexpr float kBinScale = 512.0f;           // bin = floor((s + 1) * 512), clamped
+constexpr int kBinsF = 512;                   // the fp32 sweeps (rows of up to 16 floats, similarities spread
+constexpr float kBinScaleF = 256.0f;          // widely): 32-bit counts, bin = floor((s + 1) * 256), clamped
 constexpr int kSelWaves = 4;
 constexpr int kSelRows = 16;                  // query codes per select block
 constexpr int kSel2Waves = 8;                 // the bf16 sweeps: 8 waves and
@@ -54,6 +56,7 @@ struct KnnArgs {
   int32_t V, D, DP, Vp, k, cap;
   float* Ep;            // [Vp][DP]
   uint16_t* Eh;         // [Vp][DP] bf16 (round to nearest even) of Ep, or null: the sweeps run in fp32
+  float bin_scale;      // bins per unit of similarity in the sweeps' histograms
   float* norms;         // [Vp]
   uint32_t* maxnorm;    // float bits
   int32_t* bstar;       // [Vp] lowest bin whose codes became candidates
@@ -116,7 +119,7 @@ __device__ __forceinline__ float row_eps(const KnnArgs& a, int i) {
 // bin taken, b* - 1 - m: (1 + m) bins >= 2 eps.  (Huge for rows whose eps is: everything is taken.)
 __device__ __forceinline__ int row_margin(const KnnArgs& a, int i) {
   if (!a.Eh) return 0;
-  const float m = ceilf(2.0f * row_eps(a, i) * kBinScale - 1.0f);
+  const float m = ceilf(2.0f * row_eps(a, i) * a.bin_scale - 1.0f);
   return m < (float)kBins ? (m > 0.f ? (int)m : 0) : kBins;      // (NaN norms: kBins)
 }
 
@@ -158,88 +161,122 @@ __device__ __forceinline__ int find_bstar(const uint32_t* h, int kk, int lane) {
   return bs;
 }
 
-// NS4 = float4 loads per lane and code (DP = 16 * NS4).  Contraction slot (step, g)
-// of the 16x16x4 MFMA is dimension 16*(step/4) + 4*g + step%4 on both operands.
+// b* of one row's histogram of kBinsF 32-bit counts, as find_bstar.
+__device__ __forceinline__ int find_bstar32(const uint32_t* h, int kk, int lane) {
+  // lane covers bins [511 - 8*lane - 7, 511 - 8*lane], scanned downwards
+  int cntv[8];
+  int local = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    cntv[j] = (int)h[(kBinsF - 1) - 8 * lane - j];
+    local += cntv[j];
+  }
+  int incl = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(incl, o);
+    if (lane >= o) incl += t;
+  }
+  const unsigned long long bal = __ballot(incl >= kk);
+  int bs = 0;
+  if (bal) {
+    const int fl = __ffsll((long long)bal) - 1;
+    int run = __shfl(incl - local, fl);
+    int found = 0;
+    if (lane == fl) {
+      found = kBinsF - 1 - 8 * lane - 7;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        run += cntv[j];
+        if (run >= kk) { found = kBinsF - 1 - 8 * lane - j; break; }
+      }
+    }
+    bs = __shfl(found, fl);
+  }
+  return bs;
+}
+
+// The sweeps in fp32, for rows of up to 16 floats (DP = 16: one float4 per lane and code).
+// Contraction slot (step, g) of the 16x16x4 MFMA is dimension 4*g + step on both operands.
 // A block owns 16 query codes; its 4 waves take the code tiles (16 codes each) in turn and share
 // the rows' histograms in LDS, so that a compute unit holds many waves and the latency of the
 // tile loads (served by L2: the codebook is small) is covered.  U tiles are in flight per wave.
-template <int NS4>
-__global__ __launch_bounds__(kSelWaves * 64) void knn_select_kernel(KnnArgs a) {
-  constexpr int U = NS4 <= 2 ? 4 : (NS4 <= 4 ? 2 : 1);
-  extern __shared__ uint32_t s_hist[];          // [kSelRows][kBins/2], two 16-bit counts per word
+// The sweeps are bound by the instructions issued per similarity: tiles that hold neither the
+// queries' own codes nor padding (all but two) take a path with no test and no branch per
+// similarity, and a similarity costs a multiply-add, a convert, a clamp, an address and the LDS add.
+__global__ __launch_bounds__(kSelWaves * 64) void knn_select_f32_kernel(KnnArgs a) {
+  constexpr int U = 4;
+  extern __shared__ uint32_t s_hist[];          // [kSelRows][kBinsF]
   __shared__ int s_cnt[kSelRows];
-  __shared__ int s_bstar[kSelRows];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __shared__ int s_low[kSelRows];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (tile numbers stay scalar)
   const int l16 = lane & 15, g4 = lane >> 4;
   const int row0 = blockIdx.x * kSelRows;               // the block's 16 query codes
   const int qrow = row0 + l16;                          // the lane's query code (B operand column)
-  const int DP = a.DP, V = a.V;
+  const int V = a.V;
   const int kk = a.k - 1;                               // neighbours besides the code itself
   const int ntiles = a.Vp / 16;
+  const int own_tile = row0 / 16, full_tiles = (row0 + kSelRows <= V) ? V / 16 : 0;   // plain: t != own_tile && t < full_tiles
 
-  f32x4 qv[NS4];
-#pragma unroll
-  for (int s = 0; s < NS4; ++s)
-    qv[s] = *reinterpret_cast<const f32x4*>(a.Ep + (int64_t)qrow * DP + 16 * s + 4 * g4);
+  const f32x4 qv = *reinterpret_cast<const f32x4*>(a.Ep + (int64_t)qrow * 16 + 4 * g4);
 
-  for (int i = threadIdx.x; i < kSelRows * (kBins / 2); i += kSelWaves * 64) s_hist[i] = 0u;
+  for (int i = threadIdx.x; i < kSelRows * kBinsF; i += kSelWaves * 64) s_hist[i] = 0u;
   if (threadIdx.x < kSelRows) s_cnt[threadIdx.x] = 0;
   __syncthreads();
 
-  float thr = 0.f;          // second sweep: candidates are the codes with x >= thr (bin >= b* - 1) ...
-  bool take_all = true;     // ... or all of them when b* - 1 <= 0 (bin 0 also holds NaN)
-  const float* lane_row = a.Ep + (int64_t)l16 * DP + 4 * g4;
-  uint32_t* my_hist = s_hist + l16 * (kBins / 2);
-  // One sweep over all code tiles.  PHASE 0 histograms, PHASE 1 appends.  x = (s + 1) * 512 is the bin
-  // before truncation; bin >= b is x >= b (the map is monotone), so the second sweep compares floats.
-  // Tiles that hold the query's own code or padding take a checked path; the others have no branch
-  // per similarity.
+  // second sweep: candidates are the codes with x >= thr (bin >= the lowest bin taken; -inf takes
+  // everything that is a number).  x = (s + 1) * 256 is the bin before truncation and the map is
+  // monotone, so the second sweep compares floats.
+  float thr = -INFINITY;
+  const float* lane_row = a.Ep + (int64_t)l16 * 16 + 4 * g4;
+  uint32_t* my_hist = s_hist + l16 * kBinsF;
   auto sweep = [&](auto phase_tag) {
     constexpr int PHASE = decltype(phase_tag)::value;
     for (int t0 = wave; t0 < ntiles; t0 += kSelWaves * U) {
-      f32x4 av[U][NS4];
+      f32x4 av[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int t = min(t0 + kSelWaves * u, ntiles - 1);      // (past the end: a re-read that is not used)
-        const float* arow = lane_row + (int64_t)t * (16 * DP);
-#pragma unroll
-        for (int s = 0; s < NS4; ++s) av[u][s] = *reinterpret_cast<const f32x4*>(arow + 16 * s);
+        av[u] = *reinterpret_cast<const f32x4*>(lane_row + (int64_t)t * 256);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // two chains: the matrix core stays busy
-#pragma unroll
-        for (int s = 0; s < NS4; ++s) {
-          acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][s][0], qv[s][0], acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][s][1], qv[s][1], acc1, 0, 0, 0);
-          acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][s][2], qv[s][2], acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][s][3], qv[s][3], acc1, 0, 0, 0);
-        }
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][0], qv[0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][1], qv[1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][2], qv[2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][3], qv[3], acc, 0, 0, 0);
         const int t = t0 + kSelWaves * u;
         if (t >= ntiles) continue;
         // lane holds sim(code 16 t + 4*g4 + r, query qrow), r = 0..3
         float x[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) x[r] = __builtin_fmaf(acc0[r] + acc1[r], kBinScale, kBinScale);
-        const bool plain = t != row0 / 16 && t * 16 + 16 <= V && row0 + kSelRows <= V;    // uniform
+        for (int r = 0; r < 4; ++r) x[r] = __builtin_fmaf(acc[r], kBinScaleF, kBinScaleF);
+        const bool plain = t != own_tile && t < full_tiles;    // uniform
         if (PHASE == 0) {
+          if (plain) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int code = t * 16 + 4 * g4 + r;
-            const int bin = min(max((int)x[r], 0), kBins - 1);      // (int) truncates and sends NaN to 0
-            if (plain || !(code >= V || code == qrow || qrow >= V))
-              atomicAdd(&my_hist[bin >> 1], 1u << ((bin & 1) << 4));
+            for (int r = 0; r < 4; ++r)
+              atomicAdd(&my_hist[min(max((int)x[r], 0), kBinsF - 1)], 1u);     // (int) truncates and sends NaN to 0
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int code = t * 16 + 4 * g4 + r;
+              if (!(code >= V || code == qrow || qrow >= V)) atomicAdd(&my_hist[min(max((int)x[r], 0), kBinsF - 1)], 1u);
+            }
           }
         } else {
           bool pass[4];
-          bool any = false;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int code = t * 16 + 4 * g4 + r;
-            pass[r] = (take_all || x[r] >= thr) && (plain || !(code >= V || code == qrow || qrow >= V));
-            any = any || pass[r];
+          for (int r = 0; r < 4; ++r) pass[r] = x[r] >= thr;
+          if (!plain) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int code = t * 16 + 4 * g4 + r;
+              pass[r] = pass[r] && !(code >= V || code == qrow || qrow >= V);
+            }
           }
-          if (__ballot(any)) {                                      // about one code in sixteen passes
+          if (__ballot(pass[0] || pass[1] || pass[2] || pass[3])) {   // about one code in sixteen passes
 #pragma unroll
             for (int r = 0; r < 4; ++r)
               if (pass[r]) {
@@ -251,24 +288,20 @@ __global__ __launch_bounds__(kSelWaves * 64) void knn_select_kernel(KnnArgs a) {
       }
     }
   };
-  for (int phase = 0; phase < 2; ++phase) {
-    if (phase == 0) sweep(std::integral_constant<int, 0>());
-    else sweep(std::integral_constant<int, 1>());
-    __syncthreads();
-    if (phase == 0) {
-      // b* of each row: highest bin whose count-from-the-top reaches kk; a wave takes 4 of the 16 rows
-      for (int r = wave * (kSelRows / kSelWaves); r < (wave + 1) * (kSelRows / kSelWaves); ++r) {
-        const int bs = find_bstar(s_hist + r * (kBins / 2), kk, lane);
-        if (lane == 0) {
-          s_bstar[r] = bs;
-          if (row0 + r < a.Vp) a.bstar[row0 + r] = bs - 1;
-        }
-      }
-      __syncthreads();
-      thr = (float)(s_bstar[l16] - 1);
-      take_all = s_bstar[l16] - 1 <= 0;
+  sweep(std::integral_constant<int, 0>());
+  __syncthreads();
+  // lowest bin taken, per row: b* - 1, b* the highest bin whose count from the top reaches kk; a wave takes 4 rows
+  for (int r = wave * (kSelRows / kSelWaves); r < (wave + 1) * (kSelRows / kSelWaves); ++r) {
+    const int bs = find_bstar32(s_hist + r * kBinsF, kk, lane);
+    if (lane == 0) {
+      s_low[r] = bs - 1;
+      if (row0 + r < a.Vp) a.bstar[row0 + r] = bs - 1;
     }
   }
+  __syncthreads();
+  thr = s_low[l16] <= 0 ? -INFINITY : (float)s_low[l16];      // (bin 0 also holds what is below -1)
+  sweep(std::integral_constant<int, 1>());
+  __syncthreads();
   if (threadIdx.x < kSelRows && row0 + threadIdx.x < a.Vp) a.cnt[row0 + threadIdx.x] = s_cnt[threadIdx.x];
 }
 
@@ -282,7 +315,7 @@ __global__ __launch_bounds__(kSel2Waves * 64) void knn_select_bf16_kernel(KnnArg
   extern __shared__ uint32_t s_hist[];          // [kSel2Rows][kBins/2], two 16-bit counts per word
   __shared__ int s_cnt[kSel2Rows];
   __shared__ int s_low[kSel2Rows];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (tile numbers stay scalar)
   const int l16 = lane & 15, g4 = lane >> 4;
   const int row0 = blockIdx.x * kSel2Rows;              // the block's 32 query codes (Vp is a multiple of 64)
   const int DP = a.DP, V = a.V;
@@ -301,8 +334,7 @@ __global__ __launch_bounds__(kSel2Waves * 64) void knn_select_bf16_kernel(KnnArg
   if (threadIdx.x < kSel2Rows) s_cnt[threadIdx.x] = 0;
   __syncthreads();
 
-  float thr[2] = {0.f, 0.f};
-  bool take_all[2] = {true, true};
+  float thr[2] = {-INFINITY, -INFINITY};   // second sweep: x >= thr; -inf takes everything that is a number
   const uint16_t* lane_row = a.Eh + (int64_t)l16 * DP + 8 * g4;
   auto sweep = [&](auto phase_tag) {
     constexpr int PHASE = decltype(phase_tag)::value;
@@ -337,23 +369,32 @@ __global__ __launch_bounds__(kSel2Waves * 64) void knn_select_bf16_kernel(KnnArg
           for (int r = 0; r < 4; ++r) x[r] = __builtin_fmaf(acc[qt][r], kBinScale, kBinScale);
           if (PHASE == 0) {
             uint32_t* my_hist = s_hist + (16 * qt + l16) * (kBins / 2);
+            if (plain) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const int code = t * 16 + 4 * g4 + r;
-              const int bin = min(max((int)x[r], 0), kBins - 1);      // (int) truncates and sends NaN to 0
-              if (plain || !(code >= V || code == qrow || qrow >= V))
+              for (int r = 0; r < 4; ++r) {
+                const int bin = min(max((int)x[r], 0), kBins - 1);      // (int) truncates and sends NaN to 0
                 atomicAdd(&my_hist[bin >> 1], 1u << ((bin & 1) << 4));
+              }
+            } else {
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const int code = t * 16 + 4 * g4 + r;
+                const int bin = min(max((int)x[r], 0), kBins - 1);
+                if (!(code >= V || code == qrow || qrow >= V)) atomicAdd(&my_hist[bin >> 1], 1u << ((bin & 1) << 4));
+              }
             }
           } else {
             bool pass[4];
-            bool any = false;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const int code = t * 16 + 4 * g4 + r;
-              pass[r] = (take_all[qt] || x[r] >= thr[qt]) && (plain || !(code >= V || code == qrow || qrow >= V));
-              any = any || pass[r];
+            for (int r = 0; r < 4; ++r) pass[r] = x[r] >= thr[qt];
+            if (!plain) {
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const int code = t * 16 + 4 * g4 + r;
+                pass[r] = pass[r] && !(code >= V || code == qrow || qrow >= V);
+              }
             }
-            if (__ballot(any)) {
+            if (__ballot(pass[0] || pass[1] || pass[2] || pass[3])) {
 #pragma unroll
               for (int r = 0; r < 4; ++r)
                 if (pass[r]) {
@@ -379,10 +420,7 @@ __global__ __launch_bounds__(kSel2Waves * 64) void knn_select_bf16_kernel(KnnArg
   }
   __syncthreads();
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
-    thr[qt] = (float)s_low[16 * qt + l16];
-    take_all[qt] = s_low[16 * qt + l16] <= 0;
-  }
+  for (int qt = 0; qt < 2; ++qt) thr[qt] = s_low[16 * qt + l16] <= 0 ? -INFINITY : (float)s_low[16 * qt + l16];
   sweep(std::integral_constant<int, 1>());
   __syncthreads();
   if (threadIdx.x < kSel2Rows && row0 + threadIdx.x < a.Vp) a.cnt[row0 + threadIdx.x] = s_cnt[threadIdx.x];
@@ -617,7 +655,7 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
     // can a code outside the candidate list still belong to the row?
     const int low = a.bstar[i];
     if (low >= 1) {
-      const float edge = (float)low / kBinScale - 1.0f;           // lower edge of the lowest bin taken
+      const float edge = (float)low / a.bin_scale - 1.0f;         // lower edge of the lowest bin taken
       slow = s_kth < orderable((double)edge + (double)row_eps(a, i));
     }
     if (!slow) return;
@@ -727,14 +765,12 @@ int32_t launch_select_bf16(const KnnArgs& a, hipStream_t s) {
   return LPP_OK;
 }
 
-template <int NS4>
-int32_t launch_select(const KnnArgs& a, hipStream_t s) {
-  const size_t lds = (size_t)kSelRows * (kBins / 2) * sizeof(uint32_t);
-  auto kern = knn_select_kernel<NS4>;
+int32_t launch_select_f32(const KnnArgs& a, hipStream_t s) {
+  const size_t lds = (size_t)kSelRows * kBinsF * sizeof(uint32_t);
   static LppLdsLimit limit;
-  const int32_t st = lpp_ensure_lds(reinterpret_cast<const void*>(kern), limit, lds);
+  const int32_t st = lpp_ensure_lds(reinterpret_cast<const void*>(knn_select_f32_kernel), limit, lds);
   if (st != LPP_OK) return st;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(a.Vp / kSelRows)), dim3(kSelWaves * 64), lds, s, a);
+  hipLaunchKernelGGL(knn_select_f32_kernel, dim3((unsigned)(a.Vp / kSelRows)), dim3(kSelWaves * 64), lds, s, a);
   LPP_HIP_TRY(hipGetLastError());
   return LPP_OK;
 }
@@ -761,6 +797,7 @@ extern "C" int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, in
   a.E = E; a.V = V; a.D = D; a.DP = L.DP; a.Vp = L.Vp; a.k = k; a.cap = L.cap;
   a.Ep = reinterpret_cast<float*>(w + L.o_ep);
   a.Eh = L.DP >= 32 ? reinterpret_cast<uint16_t*>(w + L.o_eh) : nullptr;
+  a.bin_scale = a.Eh ? kBinScale : kBinScaleF;
   a.norms = reinterpret_cast<float*>(w + L.o_norms);
   a.maxnorm = reinterpret_cast<uint32_t*>(w + L.o_max);
   a.bstar = reinterpret_cast<int32_t*>(w + L.o_bstar);
@@ -775,7 +812,7 @@ extern "C" int32_t lpp_build_neighbours(const float* E, int32_t V, int32_t D, in
   if (k > 1) {
     int32_t st;
     switch (L.DP / 16) {
-      case 1: st = launch_select<1>(a, s); break;
+      case 1: st = launch_select_f32(a, s); break;
       case 2: st = launch_select_bf16<1>(a, s); break;
       case 4: st = launch_select_bf16<2>(a, s); break;
       case 8: st = launch_select_bf16<4>(a, s); break;
