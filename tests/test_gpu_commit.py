@@ -48,6 +48,29 @@ def test_commit_after_verify_matches_oracle(idx, kv):
     assert np.array_equal(_host(t["vc"], cfg), vc)
 
 
+def test_commit_after_a_walk_that_gave_up_commits_the_root_only():
+    # accept_len = -1 and path = -1 are what lpp_relaxed_verify writes for an item whose walk gave
+    # up: the commit must treat it as "nothing accepted" (root only), like the oracle on a length of 0.
+    cfg = CONFIGS[1]
+    parent = static_tree(cfg.branching, cfg.N)
+    tree = lpp.Tree(parent)
+    B, H, M, S, Dh = cfg.B, cfg.H, cfg.M, cfg.S, cfg.Dh
+    att = make_attention_inputs(cfg)
+    depth = max(tree.depth, 1)
+    path = np.full((B, depth), -1, dtype=np.int32)
+    acc = np.full((B,), -1, dtype=np.int32)
+    seq_len = np.full((B,), S - 5, dtype=np.int32)
+    t, dtype = _device_kv(att, cfg)
+    new_len = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    lpp.lpp_commit_kv(tree, dtype, t["kt"], t["vt"], dev(path), dev(acc), dev(seq_len), B, H, S, Dh, t["kc"], t["vc"],
+                      new_len)
+    torch.cuda.synchronize()
+    kc, vc, nl = commit_kv(att["kc"], att["vc"], att["kt"], att["vt"], np.zeros_like(path), np.zeros_like(acc), seq_len)
+    assert np.array_equal(new_len.cpu().numpy(), nl) and np.all(nl == S - 4)
+    assert np.array_equal(_host(t["kc"], cfg), kc)
+    assert np.array_equal(_host(t["vc"], cfg), vc)
+
+
 def test_commit_argument_errors():
     cfg = CONFIGS[1]
     parent = static_tree(cfg.branching, cfg.N)
