@@ -588,13 +588,18 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
       double acc = 0.0;
       if (CH == 16) {
         // rows of 16 floats are one 64-byte segment: every lane reads its own candidate's row, no tile
+        // (Dimensions past D are zero in both rows of the padded copy, and a product of zeros added
+        // to the chain leaves it as it is -- the chain starts at +0 and can never be -0 -- so whole
+        // groups of four are taken with no test per dimension, and only the groups that hold any.)
         const float* er = a.Ep + (int64_t)jown * DP;
+        const int nq = (D + 3) >> 2;                     // uniform
         f32x4 v[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const f32x4*>(er + 4 * q);
-        if (D == 16) {
+        for (int q = 0; q < 4; ++q)
+          if (q < nq) v[q] = *reinterpret_cast<const f32x4*>(er + 4 * q);
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < 4; ++q)
+          if (q < nq) {
             const f64x2 e0 = *reinterpret_cast<const f64x2*>(eid + 4 * q);
             const f64x2 e1 = *reinterpret_cast<const f64x2*>(eid + 4 * q + 2);
             acc = __builtin_fma(e0[0], (double)v[q][0], acc);
@@ -602,13 +607,6 @@ __global__ __launch_bounds__(kRankThreads) void knn_rank_kernel(KnnArgs a, int P
             acc = __builtin_fma(e1[0], (double)v[q][2], acc);
             acc = __builtin_fma(e1[1], (double)v[q][3], acc);
           }
-        } else {
-#pragma unroll
-          for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (4 * q + e < D) acc = __builtin_fma(eid[4 * q + e], (double)v[q][e], acc);
-        }
         if (c < n) { skey[c] = orderable(acc); sidx[c] = (uint16_t)jown; }
         continue;
       }
