@@ -720,6 +720,14 @@ AttnPlan plan_attention(const lpp_tree* tree, int B, int H, int S, int Dh, int l
   if (p.mtiles <= 4 || Dh != 64) {
     p.nt = p.mtiles == 1 ? 1 : 2;
     p.msplits = (p.mtiles + p.nt - 1) / p.nt;
+    // Few heads (a quarter of the compute units or fewer would get a block): one tile per wave and
+    // twice the row ranges fill the chip with blocks that need no more key splits than before.
+    // (Head size 64 only: measured slower at 128, where a one-tile wave holds as many registers.)
+    if (Dh == 64 && p.nt == 2 &&
+        (int64_t)B * H * p.msplits * std::max(1, std::min(layers, kLayersPerLaunch)) * 4 <= tree->n_cu) {
+      p.nt = 1;
+      p.msplits = p.mtiles;
+    }
   } else {
     p.msplits = (p.mtiles + 4) / 5;
     p.nt = (p.mtiles + p.msplits - 1) / p.msplits;
