@@ -26,10 +26,10 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 # the commands: profiles/verify_attention_hbm_bytes_all_configs.txt).  They hold for the plain step
 # (one layer, multi-head, no front end, default options); otherwise the bench reports null.
 TRAFFIC = {1: {"tree_attention": 4.49e6, "relaxed_verify": 0.35e6},
-           2: {"tree_attention": 5.13e6, "relaxed_verify": 3.42e6},
-           3: {"tree_attention": 29.14e6, "relaxed_verify": 30.20e6},
-           4: {"tree_attention": 50.37e6, "relaxed_verify": 4.17e6},
-           5: {"tree_attention": 450.46e6, "relaxed_verify": 256.40e6}}
+           2: {"tree_attention": 5.08e6, "relaxed_verify": 3.40e6},
+           3: {"tree_attention": 29.14e6, "relaxed_verify": 30.21e6},
+           4: {"tree_attention": 50.37e6, "relaxed_verify": 4.19e6},
+           5: {"tree_attention": 450.42e6, "relaxed_verify": 256.42e6}}
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
